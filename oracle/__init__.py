@@ -1,0 +1,15 @@
+"""CPU oracle for draft-tree verification.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, fp64 numpy.  It defines what the GPU library must compute and shares no code with it.
+Only the tests, the smoke check and the benchmark's cpu_baseline leg may import this package; the
+product path never does.
+
+Pinned parts (see tests/test_oracle_pins.py): every function below is pinned by closed forms,
+library special cases, brute force on tiny trees or the chain == autoregressive invariant.
+Parity unpinned: none.
+"""
+from .decoder import (  # noqa: F401
+    widen, rmsnorm, rope, silu, masked_attention, ancestor_mask, node_depths,
+    forward_rows, prefill, verify_tree, autoregressive_logits, autoregressive_decode,
+)
+from .accept import argmax_margin, accept_walk, compact_rows  # noqa: F401

@@ -1,0 +1,361 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Closed forms, library special cases (torch CPU fp64 ops), brute force over all tiny trees, the
+chain == autoregressive invariant and the losslessness property of Sec. 2.4.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from ded_inputs import (ModelConfig, all_trees, chain_tree, make_weights, random_tree, tree_depths)
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ----------------------------------------------------------------------------- small pieces
+
+
+def test_widen_bf16_bits_exact():
+    # 0x3F80 = 1.0, 0xC000 = -2.0, 0x3DCD ~ 0.10009765625 in bf16
+    got = oracle.widen(np.array([0x3F80, 0xC000, 0x3DCD, 0x0000], dtype=np.uint16))
+    assert got.dtype == np.float64
+    assert got.tolist() == [1.0, -2.0, 0.10009765625, 0.0]
+
+
+def test_rmsnorm_closed_forms():
+    g = np.array([1.0, 2.0, 3.0, 4.0], dtype=np.float32)
+    # constant row c: mean square = c^2  ->  y = c / sqrt(c^2 + eps) * g
+    y = oracle.rmsnorm(np.full((1, 4), 3.0), g, 1e-5)
+    assert np.allclose(y[0], 3.0 / np.sqrt(9.0 + 1e-5) * g, rtol=0, atol=1e-15)
+    # 3-4-0-0 row: mean square = 25/4
+    y = oracle.rmsnorm(np.array([[3.0, 4.0, 0.0, 0.0]]), np.ones(4, np.float32), 0.0)
+    assert np.allclose(y[0], np.array([3.0, 4.0, 0, 0]) / 2.5, atol=1e-15)
+    # library: torch rms_norm
+    x = _rng(0).standard_normal((5, 16))
+    gg = _rng(1).standard_normal(16).astype(np.float32)
+    ref = F.rms_norm(torch.from_numpy(x), (16,), torch.from_numpy(gg.astype(np.float64)), 1e-5).numpy()
+    assert np.allclose(oracle.rmsnorm(x, gg, 1e-5), ref, atol=1e-13)
+
+
+def test_silu_library():
+    a = _rng(2).standard_normal(100) * 4
+    assert np.allclose(oracle.silu(a), F.silu(torch.from_numpy(a)).numpy(), atol=1e-14)
+    assert oracle.silu(np.array([0.0]))[0] == 0.0
+
+
+def test_rope_properties_and_complex_form():
+    hd, base = 16, 10000.0
+    g = _rng(3)
+    q = g.standard_normal((1, 1, hd))
+    k = g.standard_normal((1, 1, hd))
+    # position 0 is the identity; rotations preserve the norm
+    assert np.array_equal(oracle.rope(q, np.array([0]), base), q)
+    assert np.isclose(np.linalg.norm(oracle.rope(q, np.array([37]), base)), np.linalg.norm(q), atol=1e-12)
+    # relative-position property
+    def dot(p1, p2):
+        return float(np.sum(oracle.rope(q, np.array([p1]), base) * oracle.rope(k, np.array([p2]), base)))
+    assert np.isclose(dot(5, 2), dot(103, 100), atol=1e-10)
+    assert np.isclose(dot(9, 9), float(np.sum(q * k)), atol=1e-10)
+    assert not np.isclose(dot(5, 2), dot(5, 3), atol=1e-6)
+    # complex form: (x_i + 1j x_{i+hd/2}) * exp(1j * pos * base^(-2i/hd))
+    pos = np.array([0, 1, 7, 1000])
+    x = g.standard_normal((4, 3, hd))
+    half = hd // 2
+    xc = torch.complex(torch.from_numpy(x[..., :half]), torch.from_numpy(x[..., half:]))
+    theta = torch.tensor(base, dtype=torch.float64) ** (-torch.arange(half, dtype=torch.float64) * 2 / hd)
+    rot = torch.polar(torch.ones(4, half, dtype=torch.float64),
+                      torch.from_numpy(pos).to(torch.float64)[:, None] * theta[None, :])
+    yc = xc * rot[:, None, :]
+    ref = torch.cat([yc.real, yc.imag], dim=-1).numpy()
+    assert np.allclose(oracle.rope(x, pos, base), ref, atol=1e-12)
+    # hd = 2: one plane, angle = pos
+    y = oracle.rope(np.array([[[1.0, 0.0]]]), np.array([1]), base)
+    assert np.allclose(y[0, 0], [np.cos(1.0), np.sin(1.0)], atol=1e-15)
+
+
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (4, 2), (6, 1)])
+def test_masked_attention_vs_torch_sdpa(H, Hkv):
+    g = _rng(4)
+    n, m, hd = 7, 19, 8
+    q = g.standard_normal((n, H, hd))
+    k = g.standard_normal((m, Hkv, hd))
+    v = g.standard_normal((m, Hkv, hd))
+    vis = g.random((n, m)) < 0.5
+    vis[:, 0] = True
+    got = oracle.masked_attention(q, k, v, vis)
+    rep = H // Hkv
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(rep, dim=0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(rep, dim=0)[None]
+    ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=torch.from_numpy(vis)[None, None])
+    assert np.allclose(got, ref[0].permute(1, 0, 2).numpy(), atol=1e-12)
+
+
+def test_masked_attention_zero_query_is_mean_of_visible_values():
+    g = _rng(5)
+    n, m, H, hd = 4, 9, 2, 4
+    v = g.standard_normal((m, H, hd))
+    k = g.standard_normal((m, H, hd))
+    vis = np.zeros((n, m), dtype=bool)
+    for i in range(n):
+        vis[i, : i + 3] = True
+    out = oracle.masked_attention(np.zeros((n, H, hd)), k, v, vis)
+    for i in range(n):
+        assert np.allclose(out[i], v[: i + 3].mean(axis=0), atol=1e-14)
+
+
+def test_ancestor_mask_and_depths():
+    parent = np.array([-1, 0, 0, 1, 1, 2, 5])
+    A = oracle.ancestor_mask(parent)
+    expect = {0: [0], 1: [0, 1], 2: [0, 2], 3: [0, 1, 3], 4: [0, 1, 4], 5: [0, 2, 5], 6: [0, 2, 5, 6]}
+    for i, cols in expect.items():
+        assert np.flatnonzero(A[i]).tolist() == cols
+    d = oracle.node_depths(parent)
+    assert d.tolist() == [0, 1, 1, 2, 2, 2, 3]
+    for seed in range(5):
+        p = random_tree(40, None, seed)
+        A = oracle.ancestor_mask(p)
+        assert (A.sum(axis=1) == oracle.node_depths(p) + 1).all()
+        # transitively closed, lower-triangular, reflexive
+        assert ((A.astype(int) @ A.astype(int) > 0) == A).all()
+        assert not np.triu(A, 1).any() and A.diagonal().all()
+
+
+# ----------------------------------------------------------------------------- whole forward
+
+
+def _torch_layer_stack(cfg, w, tokens):
+    """Independent causal forward built from torch library ops (fp64)."""
+    T = lambda a: torch.from_numpy(oracle.widen(a))
+    n, H, Hkv, hd = len(tokens), cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    x = T(w["emb"])[torch.as_tensor(np.asarray(tokens), dtype=torch.long)]
+    half = hd // 2
+    theta = torch.tensor(cfg.rope_base, dtype=torch.float64) ** (-torch.arange(half, dtype=torch.float64) * 2 / hd)
+    rot = torch.polar(torch.ones(n, half, dtype=torch.float64),
+                      torch.arange(n, dtype=torch.float64)[:, None] * theta[None])
+
+    def rope(t):  # [n][heads][hd]
+        c = torch.complex(t[..., :half], t[..., half:]) * rot[:, None, :]
+        return torch.cat([c.real, c.imag], dim=-1)
+
+    for lw in w["layers"]:
+        y = F.rms_norm(x, (cfg.d_model,), T(lw["norm_attn"]), cfg.rms_eps)
+        q = rope(F.linear(y, T(lw["wq"])).view(n, H, hd)).transpose(0, 1)[None]
+        k = rope(F.linear(y, T(lw["wk"])).view(n, Hkv, hd)).transpose(0, 1)[None]
+        v = F.linear(y, T(lw["wv"])).view(n, Hkv, hd).transpose(0, 1)[None]
+        o = F.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=(H != Hkv))
+        x = x + F.linear(o[0].transpose(0, 1).reshape(n, H * hd), T(lw["wo"]))
+        y = F.rms_norm(x, (cfg.d_model,), T(lw["norm_ffn"]), cfg.rms_eps)
+        x = x + F.linear(F.silu(F.linear(y, T(lw["wg"]))) * F.linear(y, T(lw["wu"])), T(lw["wd"]))
+    return F.linear(F.rms_norm(x, (cfg.d_model,), T(w["final_norm"]), cfg.rms_eps), T(w["lm_head"])).numpy()
+
+
+def test_prefill_vs_torch_library_stack(small_cfg, small_model):
+    tokens = _rng(6).integers(0, small_cfg.vocab, 11)
+    logits, k, v = oracle.prefill(small_cfg, small_model, tokens)
+    ref = _torch_layer_stack(small_cfg, small_model, tokens)
+    assert np.allclose(logits, ref, atol=1e-10)
+    assert np.abs(ref).max() > 0.1  # the comparison is not vacuous
+
+
+def test_bf16_weights_are_consumed_exactly():
+    cfg = ModelConfig("pin-bf16", 1, 16, 2, 2, 8, 24, 20, dtype="bf16")
+    w = make_weights(cfg, seed=1, std=0.3)
+    assert w["emb"].dtype == np.uint16
+    tokens = [3, 5, 7]
+    ref = _torch_layer_stack(cfg, w, tokens)
+    assert np.allclose(oracle.prefill(cfg, w, tokens)[0], ref, atol=1e-10)
+
+
+def test_zero_layer_model_closed_form():
+    cfg = ModelConfig("pin-L0", 0, 8, 2, 2, 4, 8, 12, dtype="fp32")
+    w = make_weights(cfg, seed=2, gain_jitter=0.2, std=0.5)
+    tok = np.array([4, 4, 9])
+    logits, _, _ = oracle.verify_tree(cfg, w, np.array([-1, 0, 0]), tok)
+    e = w["emb"].astype(np.float64)[tok]
+    hand = (e / np.sqrt((e * e).mean(-1, keepdims=True) + cfg.rms_eps) * w["final_norm"]) @ w["lm_head"].astype(np.float64).T
+    assert np.allclose(logits, hand, atol=1e-13)
+    assert np.array_equal(logits[0], logits[1])
+
+
+def test_chain_tree_equals_autoregressive(small_cfg, small_model):
+    g = _rng(7)
+    prefix = g.integers(0, small_cfg.vocab, 6)
+    chain = g.integers(0, small_cfg.vocab, 5)
+    _, pk, pv = oracle.prefill(small_cfg, small_model, prefix)
+    logits, _, _ = oracle.verify_tree(small_cfg, small_model, chain_tree(5), chain, pk, pv)
+    ar = oracle.autoregressive_logits(small_cfg, small_model, np.concatenate([prefix, chain]))
+    assert np.allclose(logits, ar[len(prefix):], atol=1e-10)
+    # P = 0: the root attends to itself only
+    logits0, _, _ = oracle.verify_tree(small_cfg, small_model, chain_tree(4), chain[:4])
+    assert np.allclose(logits0, oracle.autoregressive_logits(small_cfg, small_model, chain[:4]), atol=1e-10)
+
+
+def _path(parent, i):
+    out = []
+    while i >= 0:
+        out.append(i)
+        i = int(parent[i])
+    return out[::-1]
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_brute_force_all_tiny_trees(small_cfg, small_model, n):
+    """Row i of the tree forward == last row of plain autoregressive decoding over prefix + path(i)."""
+    g = _rng(8 + n)
+    prefix = g.integers(0, small_cfg.vocab, 4)
+    _, pk, pv = oracle.prefill(small_cfg, small_model, prefix)
+    for parent in all_trees(n):
+        token = g.integers(0, small_cfg.vocab, n)
+        logits, _, _ = oracle.verify_tree(small_cfg, small_model, parent, token, pk, pv)
+        for i in range(n):
+            seq = np.concatenate([prefix, token[_path(parent, i)]])
+            ar = oracle.autoregressive_logits(small_cfg, small_model, seq)[-1]
+            assert np.allclose(logits[i], ar, atol=1e-10), (parent, i)
+
+
+def test_sibling_permutation_invariance(small_cfg, small_model):
+    g = _rng(20)
+    prefix = g.integers(0, small_cfg.vocab, 5)
+    _, pk, pv = oracle.prefill(small_cfg, small_model, prefix)
+    parent = np.array([-1, 0, 0, 0, 1, 1, 3, 4])
+    token = g.integers(0, small_cfg.vocab, 8)
+    base, _, _ = oracle.verify_tree(small_cfg, small_model, parent, token, pk, pv)
+    # swap siblings 1 <-> 3 (children of the root): relabel and keep parent < child
+    perm = [0, 3, 2, 1, 6, 4, 5, 7]  # new index -> old index (children re-attached accordingly)
+    old_to_new = {o: nidx for nidx, o in enumerate(perm)}
+    parent2 = np.array([-1 if parent[o] < 0 else old_to_new[int(parent[o])] for o in perm])
+    assert all(parent2[i] < i for i in range(1, 8))
+    token2 = token[perm]
+    got, _, _ = oracle.verify_tree(small_cfg, small_model, parent2, token2, pk, pv)
+    assert np.allclose(got, base[perm], atol=1e-11)
+
+
+# ----------------------------------------------------------------------------- argmax / walk
+
+
+def test_argmax_margin():
+    x = np.array([[0.5, 2.0, 2.0, -1.0], [3.0, 1.0, 2.5, 2.75]])
+    a, m = oracle.argmax_margin(x)
+    assert a.tolist() == [1, 0]  # lowest index on the exact tie
+    assert np.allclose(m, [0.0, 0.25])
+    r = _rng(21).standard_normal((9, 301))
+    a, m = oracle.argmax_margin(r)
+    s = np.sort(r, axis=1)
+    assert (a == np.argmax(r, axis=1)).all() and np.allclose(m, s[:, -1] - s[:, -2])
+    with pytest.raises(ValueError):
+        oracle.argmax_margin(np.array([[1.0, np.nan]]))
+
+
+def _parse_cases():
+    cases = []
+    for line in open(os.path.join(GOLDEN, "accept_walk_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        fields = {}
+        key = None
+        for tok in line.split():
+            if tok.endswith(":"):
+                key = tok[:-1]
+                fields[key] = []
+            else:
+                fields[key].append(int(tok))
+        cases.append(fields)
+    return cases
+
+
+def test_accept_walk_hand_cases():
+    cases = _parse_cases()
+    assert len(cases) == 6
+    for c in cases:
+        acc, path = oracle.accept_walk(c["parent"], c["token"], c["model"])
+        assert path == c["path"] and acc == c["accepted"], c
+
+
+def _walk_brute(parent, token, a):
+    """Enumerate every root->node path, keep those whose draft tokens all match, take the deepest."""
+    best = None
+    for v in range(len(parent)):
+        p = _path(parent, v)
+        if all(token[p[j]] == a[p[j - 1]] for j in range(1, len(p))):
+            if best is None or len(p) > len(best):
+                best = p
+    return [int(token[v]) for v in best[1:]] + [int(a[best[-1]])], best
+
+
+def test_accept_walk_brute_force():
+    g = _rng(22)
+    for trial in range(300):
+        n = int(g.integers(1, 9))
+        parent = random_tree(n, None, seed=trial)
+        token = g.integers(0, 3, n)
+        a = g.integers(0, 3, n)
+        assert oracle.accept_walk(parent, token, a) == _walk_brute(parent, token, a)
+
+
+def test_compact_rows():
+    pre = np.arange(6).reshape(3, 2)
+    tree = 100 + np.arange(10).reshape(5, 2)
+    out = oracle.compact_rows(pre, tree, [0, 2, 4])
+    assert out.tolist() == [[0, 1], [2, 3], [4, 5], [100, 101], [104, 105], [108, 109]]
+
+
+# ----------------------------------------------------------------------------- losslessness
+
+
+def test_planted_tree_and_lossless_multi_step(small_cfg, small_model):
+    """Sec. 2.4: the verified output equals plain autoregressive greedy decoding, whatever the drafts."""
+    cfg, w = small_cfg, small_model
+    g = _rng(23)
+    prompt = g.integers(0, cfg.vocab, 5).tolist()
+    n_new = 12
+    ar = oracle.autoregressive_decode(cfg, w, prompt, n_new)
+
+    # state: cache holds prompt[:-1]; the root is the last prompt token
+    _, pk, pv = oracle.prefill(cfg, w, prompt[:-1])
+    root = prompt[-1]
+    produced = []
+    step = 0
+    while len(produced) < n_new:
+        # draft tree: one branch carries the true continuation for m tokens, then a wrong token;
+        # other branches are random
+        m = step % 4
+        known = ar[len(produced): len(produced) + m]
+        m = len(known)
+        parent = [-1] + list(range(m))
+        token = [root] + list(known)
+        planted = list(range(m + 1))
+        nxt_true = ar[len(produced) + m] if len(produced) + m < len(ar) else 0
+        parent.append(m)
+        token.append((nxt_true + 1) % cfg.vocab)  # a wrong draft token below the planted branch
+        for _ in range(4):  # random extra nodes
+            parent.append(int(g.integers(0, len(token))))
+            wrong = int(g.integers(0, cfg.vocab))
+            token.append(wrong)
+        # random nodes might accidentally extend the accepted path correctly; that is still lossless
+        logits, kr, vr = oracle.verify_tree(cfg, w, np.array(parent), np.array(token), pk, pv)
+        a, _ = oracle.argmax_margin(logits)
+        acc, path = oracle.accept_walk(parent, token, a)
+        assert path[: m + 1] == planted
+        assert len(acc) >= m + 1
+        produced.extend(acc)
+        pk = [oracle.compact_rows(pk[l], kr[l], path) for l in range(cfg.n_layers)]
+        pv = [oracle.compact_rows(pv[l], vr[l], path) for l in range(cfg.n_layers)]
+        root = acc[-1]
+        step += 1
+    assert produced[:n_new] == ar
+    # the cache after the steps equals a plain prefill of the same tokens
+    seq = (prompt + produced)[: len(pk[0])]
+    _, fk, fv = oracle.prefill(cfg, w, seq)
+    for l in range(cfg.n_layers):
+        assert np.allclose(pk[l], fk[l], atol=1e-10) and np.allclose(pv[l], fv[l], atol=1e-10)
