@@ -1,0 +1,174 @@
+/*
+ * ded_verify.h — C ABI of the MI355X (gfx950) draft-tree verification library.
+ *
+ * The library implements the verification stage of adaptive draft-verification decoding
+ * (Sec. 2.4, "Draft Construction and Verification"): the target decoder runs ONE forward pass over a
+ * pseudo-sequence that holds every draft token once, under a tree-attention mask that lets a draft
+ * token see the context and its own ancestors only; then the model's own token at every node is
+ * compared with the draft tokens below it and the longest approved path is kept.  The target models
+ * are Llama-2 / Vicuna style decoders (Sec. 4.1): pre-norm, RMSNorm, rotary positions, (grouped-query)
+ * soft-max attention, SwiGLU feed-forward, untied LM head.  Sampling is greedy (Sec. 4.1 default).
+ *
+ * Conventions
+ *   - One GPU, one HIP stream per context.  A context is not re-entrant.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library allocates no device memory: everything it needs lives in the
+ *     caller's workspace (ded_workspace_bytes) and KV buffers (ded_kv_layer_bytes).
+ *   - Every call returns DED_OK (0) or a negative DED_E* code; nothing throws or aborts.
+ *     All argument validation happens on the host before the first kernel launch.
+ *   - Same inputs give bit-identical argmax, accepted tokens and compaction indices (fixed
+ *     reduction orders, no floating-point atomics).
+ *   - Tree encoding: node 0 is the root = the last committed token, whose K/V is not in the cache
+ *     yet (parent[0] = -1, depth 0, position prefix_len).  Nodes 1..n-1 are draft tokens with
+ *     0 <= parent[i] < i.  Node i sits at position prefix_len + depth(i).
+ */
+#ifndef DED_VERIFY_H
+#define DED_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DED_OK = 0,
+  DED_EINVAL = -1, /* null pointer, bad shape or unsupported configuration */
+  DED_ETREE = -2,  /* malformed parent array */
+  DED_ETOKEN = -3, /* token id outside [0, vocab) */
+  DED_ECAP = -4,   /* prefix_len + n_nodes exceeds kv_capacity, or a size exceeds its maximum */
+  DED_ESTATE = -5, /* call out of order (e.g. ded_accept without a pending step) */
+  DED_EHIP = -6,   /* a HIP runtime call failed */
+  DED_ENOMEM = -7  /* workspace too small / host allocation failed */
+};
+
+enum { DED_F32 = 0, DED_BF16 = 1 };
+
+typedef struct ded_ctx ded_ctx; /* opaque */
+
+/* Model and capacity description.  dtype is the storage type of the weight matrices, of the KV
+ * cache and of the GEMM inputs (accumulation, residual stream, norms and soft-max statistics are
+ * always fp32).  DED_BF16 needs head_dim == 128, d_model % 128 == 0, d_ffn % 128 == 0,
+ * vocab % 16 == 0 and kv_capacity % 64 == 0; max_nodes <= 256. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_base; /* rotary base; pairing is (i, i + head_dim/2), angle pos * base^(-2i/head_dim) */
+  float rms_eps;
+  int32_t dtype; /* DED_F32 or DED_BF16 */
+  int32_t max_batch;
+  int32_t kv_capacity; /* cache slots per sequence */
+  int32_t max_nodes;   /* largest tree (root included) per sequence */
+} ded_config;
+
+/* Weights, device memory, row-major, every linear map stored [out_features][in_features] (y = W x),
+ * in the config's dtype; norm gains are fp32.  The per-layer members are HOST arrays of n_layers
+ * device pointers.  ded_verify_init re-lays the matrices out inside the workspace; after it returns
+ * the caller may release or overwrite these buffers.
+ *   wqkv[l]     [(H + 2 Hkv) * hd][d]  rows: all query heads, then all key heads, then all value heads
+ *   wo[l]       [d][H * hd]
+ *   wgate_up[l] [2 F][d]               rows: gate projection, then up projection
+ *   wdown[l]    [d][F]                                                                    */
+typedef struct {
+  const void *emb;         /* [vocab][d] */
+  const void *lm_head;     /* [vocab][d] */
+  const float *final_norm; /* [d] */
+  const void *const *wqkv;
+  const void *const *wo;
+  const void *const *wgate_up;
+  const void *const *wdown;
+  const float *const *norm_attn; /* [n_layers] -> [d] */
+  const float *const *norm_ffn;  /* [n_layers] -> [d] */
+} ded_weights;
+
+/* KV cache: HOST arrays of n_layers device buffers, each ded_kv_layer_bytes(cfg) bytes, holding
+ * max_batch sequences of kv_capacity slots.  The element layout inside a buffer belongs to the
+ * library (bf16 caches are stored as matrix-core operand fragments); use ded_kv_store / ded_kv_load
+ * to move plain [Hkv][n][hd] rows in and out.  Keys are stored after the rotary embedding. */
+typedef struct {
+  void *const *k;
+  void *const *v;
+} ded_kv;
+
+/* Sizes the caller must allocate (bytes of device memory). 0 on an invalid config. */
+size_t ded_workspace_bytes(const ded_config *cfg);
+size_t ded_kv_layer_bytes(const ded_config *cfg);
+
+/* Host-only check of a step's arguments (the same check ded_verify_step performs before it launches
+ * anything): DED_OK, DED_EINVAL, DED_ETREE, DED_ETOKEN or DED_ECAP.  Touches no device. */
+int ded_validate_tree(const ded_config *cfg, int32_t batch, const int32_t *prefix_len,
+                      const int32_t *n_nodes, const int32_t *parent, const int32_t *token);
+
+/* Creates a context: validates cfg, re-lays out the weights into `workspace` (device, 256-byte
+ * aligned, >= ded_workspace_bytes) on `hip_stream` (a hipStream_t; NULL = the default stream) and
+ * waits for that to finish.  The workspace and KV buffers must outlive the context; their contents
+ * are the library's while the context lives.  Errors: DED_EINVAL, DED_ENOMEM, DED_EHIP. */
+int ded_verify_init(const ded_config *cfg, const ded_weights *weights, const ded_kv *kv,
+                    void *workspace, size_t workspace_bytes, void *hip_stream, ded_ctx **out);
+void ded_verify_free(ded_ctx *ctx);
+
+/* The verification forward of Sec. 2.4, enqueued on the context's stream (asynchronous).
+ *   batch       number of sequences, 1..max_batch; sequence b uses cache slot range b
+ *   prefix_len  host [batch]: tokens already in the cache of sequence b
+ *   n_nodes     host [batch]: tree rows of sequence b, 1..max_nodes (root included)
+ *   parent      host [batch][max_nodes]: parent[0] = -1, 0 <= parent[i] < i
+ *   token       host [batch][max_nodes]: token ids, token[0] = the root token
+ *   logits_out  device fp32 [batch][max_nodes][vocab] or NULL; when given, the rows of the real
+ *               nodes are written there (rows of absent nodes are left untouched)
+ * Effects: K/V of node i of sequence b are written to cache slot prefix_len[b] + i (scratch until
+ * accepted); the per-node argmax and top-1/top-2 margin are kept in the workspace.
+ * Errors: DED_EINVAL, DED_ETREE, DED_ETOKEN, DED_ECAP, DED_EHIP.  On error nothing was launched. */
+int ded_verify_step(ded_ctx *ctx, int32_t batch, const int32_t *prefix_len, const int32_t *n_nodes,
+                    const int32_t *parent, const int32_t *token, float *logits_out);
+
+/* Approval walk + cache compaction for the pending step (Sec. 2.4: a draft token is approved when
+ * it equals the model's token at its parent; the draft is discarded from the first mismatch on).
+ *   mode 0  greedy walk: end node = the deepest approved node (lowest index among equally deep);
+ *   mode 1  force-accept: the tree must be a chain and all of it is kept (chunked prefill).
+ * Outputs (host; stride = max_nodes + 1 per sequence):
+ *   accepted_tokens [batch][max_nodes+1]  draft tokens on the kept path below the root, then the
+ *                                         model's own token at the end node (the next root)
+ *   n_accepted      [batch]               number of tokens written (path length)
+ *   compaction_idx  [batch][max_nodes+1]  node indices of the kept path, root first
+ *   new_prefix_len  [batch]               prefix_len + path length
+ * The K/V of path node j move to slot prefix_len + j; slots beyond new_prefix_len are dead.
+ * Synchronises the stream.  Errors: DED_EINVAL, DED_ESTATE, DED_ETREE (mode 1, not a chain), DED_EHIP. */
+int ded_accept(ded_ctx *ctx, int32_t mode, int32_t *accepted_tokens, int32_t *n_accepted,
+               int32_t *compaction_idx, int32_t *new_prefix_len);
+
+/* Per-node model tokens of the last step: argmax host [batch][max_nodes] (lowest id on exact ties),
+ * margin host [batch][max_nodes] or NULL (top-1 minus top-2 logit).  Synchronises the stream. */
+int ded_get_argmax(ded_ctx *ctx, int32_t *argmax, float *margin);
+
+/* Plain <-> library layout for `n` cache slots starting at `first_slot` of sequence `seq`, layer
+ * `layer`.  k_plain / v_plain: device [Hkv][n][hd] in the config's dtype (either may be NULL).
+ * Asynchronous on the context's stream.  Errors: DED_EINVAL, DED_ECAP, DED_EHIP. */
+int ded_kv_store(ded_ctx *ctx, int32_t layer, int32_t seq, int32_t first_slot, int32_t n,
+                 const void *k_plain, const void *v_plain);
+int ded_kv_load(ded_ctx *ctx, int32_t layer, int32_t seq, int32_t first_slot, int32_t n,
+                void *k_plain, void *v_plain);
+
+/* Tree-masked attention of ONE layer on its own (Sec. 2.4, the tree-attention mask), for queries
+ * and tree K/V supplied by the caller: q device [batch][max_nodes][H][hd], k_tree / v_tree device
+ * [batch][Hkv][max_nodes][hd] (already rotated), all in the config's dtype; the prefix K/V are
+ * whatever the cache of `layer` holds in slots [0, prefix_len).  The tree K/V are first written to
+ * slots prefix_len + i.  out device [batch][max_nodes][H][hd], config dtype.  Asynchronous.
+ * Errors as ded_verify_step. */
+int ded_tree_attention(ded_ctx *ctx, int32_t layer, int32_t batch, const int32_t *prefix_len,
+                       const int32_t *n_nodes, const int32_t *parent, const void *q,
+                       const void *k_tree, const void *v_tree, void *out);
+
+/* Kernel timing.  While enabled, every kernel launch of the forward is bracketed by HIP events on
+ * the context's stream (this serialises nothing but adds event overhead, so use a separate pass).
+ * ded_profile_read synchronises, then fills up to `cap` entries: names[i] points to a static string,
+ * total_ms[i] is the summed duration and launches[i] the launch count since ded_profile_enable.
+ * Returns the number of kernel classes (>= 0) or a negative error. */
+int ded_profile_enable(ded_ctx *ctx, int32_t on);
+int ded_profile_read(ded_ctx *ctx, int32_t cap, const char **names, double *total_ms, int64_t *launches);
+
+const char *ded_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DED_VERIFY_H */

@@ -1,0 +1,365 @@
+"""ctypes binding of libded_verify.so: argument marshalling only.
+
+Module-level functions carry the names of the C entry points (include/ded_verify.h) and take raw
+pointers / numpy arrays; `Verifier` is a convenience holder that allocates the device buffers with
+torch (device memory and streams are all torch is used for) and keeps them alive.
+The library is required: importing works without it, but every call raises if it is not built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libded_verify.so")
+
+DED_OK, DED_EINVAL, DED_ETREE, DED_ETOKEN, DED_ECAP, DED_ESTATE, DED_EHIP, DED_ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
+DED_F32, DED_BF16 = 0, 1
+
+EXPORTS = [
+    "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_verify_init", "ded_verify_free",
+    "ded_verify_step", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
+    "ded_profile_enable", "ded_profile_read", "ded_strerror",
+]
+
+
+class ded_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
+               [("rope_base", C.c_float), ("rms_eps", C.c_float)] + \
+               [(n, C.c_int32) for n in ("dtype", "max_batch", "kv_capacity", "max_nodes")]
+
+
+class ded_weights(C.Structure):
+    _fields_ = [("emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
+                ("wgate_up", C.POINTER(C.c_void_p)), ("wdown", C.POINTER(C.c_void_p)),
+                ("norm_attn", C.POINTER(C.c_void_p)), ("norm_ffn", C.POINTER(C.c_void_p))]
+
+
+class ded_kv(C.Structure):
+    _fields_ = [("k", C.POINTER(C.c_void_p)), ("v", C.POINTER(C.c_void_p))]
+
+
+class DedError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {ded_strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the shared library (built in-tree by __graft_entry__.build()); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+        L.ded_workspace_bytes.restype = C.c_size_t
+        L.ded_workspace_bytes.argtypes = [C.POINTER(ded_config)]
+        L.ded_kv_layer_bytes.restype = C.c_size_t
+        L.ded_kv_layer_bytes.argtypes = [C.POINTER(ded_config)]
+        L.ded_validate_tree.restype = C.c_int
+        L.ded_validate_tree.argtypes = [C.POINTER(ded_config), C.c_int32, i32p, i32p, i32p, i32p]
+        L.ded_verify_init.restype = C.c_int
+        L.ded_verify_init.argtypes = [C.POINTER(ded_config), C.POINTER(ded_weights), C.POINTER(ded_kv), vp,
+                                      C.c_size_t, vp, C.POINTER(vp)]
+        L.ded_verify_free.restype = None
+        L.ded_verify_free.argtypes = [vp]
+        L.ded_verify_step.restype = C.c_int
+        L.ded_verify_step.argtypes = [vp, C.c_int32, i32p, i32p, i32p, i32p, vp]
+        L.ded_accept.restype = C.c_int
+        L.ded_accept.argtypes = [vp, C.c_int32, i32p, i32p, i32p, i32p]
+        L.ded_get_argmax.restype = C.c_int
+        L.ded_get_argmax.argtypes = [vp, i32p, C.POINTER(C.c_float)]
+        for name in ("ded_kv_store", "ded_kv_load"):
+            f = getattr(L, name)
+            f.restype = C.c_int
+            f.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+        L.ded_tree_attention.restype = C.c_int
+        L.ded_tree_attention.argtypes = [vp, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp]
+        L.ded_profile_enable.restype = C.c_int
+        L.ded_profile_enable.argtypes = [vp, C.c_int32]
+        L.ded_profile_read.restype = C.c_int
+        L.ded_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
+                                       C.POINTER(C.c_int64)]
+        L.ded_strerror.restype = C.c_char_p
+        L.ded_strerror.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p32(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def make_config(n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, rope_base, rms_eps, dtype,
+                max_batch, kv_capacity, max_nodes) -> ded_config:
+    dt = {"fp32": DED_F32, "bf16": DED_BF16}.get(dtype, dtype)
+    return ded_config(n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, rope_base, rms_eps, dt,
+                      max_batch, kv_capacity, max_nodes)
+
+
+# ---- same-named wrappers -------------------------------------------------------------------
+
+
+def ded_strerror(code: int) -> str:
+    return lib().ded_strerror(int(code)).decode()
+
+
+def ded_workspace_bytes(cfg: ded_config) -> int:
+    return int(lib().ded_workspace_bytes(C.byref(cfg)))
+
+
+def ded_kv_layer_bytes(cfg: ded_config) -> int:
+    return int(lib().ded_kv_layer_bytes(C.byref(cfg)))
+
+
+def ded_validate_tree(cfg: ded_config, prefix_len, n_nodes, parent, token) -> int:
+    """parent / token: [batch][max_nodes] int arrays (or None to exercise the null check)."""
+    pl, nn = _i32(prefix_len), _i32(n_nodes)
+    par = None if parent is None else _i32(parent)
+    tok = None if token is None else _i32(token)
+    return int(lib().ded_validate_tree(C.byref(cfg), len(pl), _p32(pl), _p32(nn), _p32(par), _p32(tok)))
+
+
+def ded_verify_init(cfg: ded_config, weights: ded_weights, kv: ded_kv, workspace_ptr: int, workspace_bytes: int,
+                    stream_ptr: int) -> int:
+    out = C.c_void_p()
+    rc = lib().ded_verify_init(C.byref(cfg), C.byref(weights) if weights is not None else None,
+                               C.byref(kv) if kv is not None else None, workspace_ptr, workspace_bytes,
+                               stream_ptr, C.byref(out))
+    if rc != DED_OK:
+        raise DedError(rc, "ded_verify_init")
+    return out.value
+
+
+def ded_verify_free(ctx: int) -> None:
+    lib().ded_verify_free(ctx)
+
+
+def ded_verify_step(ctx: int, prefix_len, n_nodes, parent, token, logits_ptr: Optional[int] = None) -> int:
+    pl, nn, par, tok = _i32(prefix_len), _i32(n_nodes), _i32(parent), _i32(token)
+    return int(lib().ded_verify_step(ctx, len(pl), _p32(pl), _p32(nn), _p32(par), _p32(tok), logits_ptr))
+
+
+def ded_accept(ctx: int, mode: int, batch: int, max_nodes: int):
+    stride = max_nodes + 1
+    acc = np.zeros((batch, stride), np.int32)
+    nacc = np.zeros(batch, np.int32)
+    path = np.zeros((batch, stride), np.int32)
+    newp = np.zeros(batch, np.int32)
+    rc = int(lib().ded_accept(ctx, mode, _p32(acc), _p32(nacc), _p32(path), _p32(newp)))
+    return rc, acc, nacc, path, newp
+
+
+def ded_get_argmax(ctx: int, batch: int, max_nodes: int):
+    a = np.full((batch, max_nodes), -1, np.int32)
+    m = np.zeros((batch, max_nodes), np.float32)
+    rc = int(lib().ded_get_argmax(ctx, _p32(a), m.ctypes.data_as(C.POINTER(C.c_float))))
+    return rc, a, m
+
+
+def ded_kv_store(ctx, layer, seq, first_slot, n, k_ptr, v_ptr) -> int:
+    return int(lib().ded_kv_store(ctx, layer, seq, first_slot, n, k_ptr, v_ptr))
+
+
+def ded_kv_load(ctx, layer, seq, first_slot, n, k_ptr, v_ptr) -> int:
+    return int(lib().ded_kv_load(ctx, layer, seq, first_slot, n, k_ptr, v_ptr))
+
+
+def ded_tree_attention(ctx, layer, prefix_len, n_nodes, parent, q_ptr, k_ptr, v_ptr, out_ptr) -> int:
+    pl, nn, par = _i32(prefix_len), _i32(n_nodes), _i32(parent)
+    return int(lib().ded_tree_attention(ctx, layer, len(pl), _p32(pl), _p32(nn), _p32(par), q_ptr, k_ptr, v_ptr,
+                                        out_ptr))
+
+
+def ded_profile_enable(ctx, on: bool) -> int:
+    return int(lib().ded_profile_enable(ctx, 1 if on else 0))
+
+
+def ded_profile_read(ctx) -> dict:
+    cap = 64
+    names = (C.c_char_p * cap)()
+    ms = (C.c_double * cap)()
+    cnt = (C.c_int64 * cap)()
+    n = int(lib().ded_profile_read(ctx, cap, names, ms, cnt))
+    if n < 0:
+        raise DedError(n, "ded_profile_read")
+    return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(min(n, cap))}
+
+
+# ---- device-buffer holder ---------------------------------------------------------------------
+
+
+def _to_device(a, device, dtype: str):
+    """numpy (fp32, or uint16 bf16 bit patterns) / torch tensor -> device tensor in storage dtype."""
+    import torch
+    if isinstance(a, np.ndarray):
+        if a.dtype == np.uint16:
+            t = torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+        else:
+            t = torch.from_numpy(np.ascontiguousarray(a)).to(device)
+    else:
+        t = a.to(device)
+    want = torch.bfloat16 if dtype == "bf16" else torch.float32
+    if t.dtype != want:
+        raise TypeError(f"tensor dtype {t.dtype} does not match the configured storage type {dtype}")
+    return t.contiguous()
+
+
+class Verifier:
+    """Owns the device buffers of one context.  model_cfg: object with n_layers, d_model, n_heads,
+    n_kv_heads, head_dim, d_ffn, vocab, rope_base, rms_eps, dtype ("fp32" | "bf16").
+    weights: {"emb", "lm_head", "final_norm", "layers": [{wq, wk, wv, wo, wg, wu, wd, norm_attn,
+    norm_ffn}]} (numpy or torch), each linear map [out][in]."""
+
+    def __init__(self, model_cfg, weights, max_batch: int, kv_capacity: int, max_nodes: int, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.mc = model_cfg
+        self.dtype = model_cfg.dtype
+        self.max_batch, self.max_nodes = max_batch, max_nodes
+        if self.dtype == "bf16":
+            kv_capacity = (kv_capacity + 63) // 64 * 64
+        self.kv_capacity = kv_capacity
+        self.cfg = make_config(model_cfg.n_layers, model_cfg.d_model, model_cfg.n_heads, model_cfg.n_kv_heads,
+                               model_cfg.head_dim, model_cfg.d_ffn, model_cfg.vocab, model_cfg.rope_base,
+                               model_cfg.rms_eps, self.dtype, max_batch, kv_capacity, max_nodes)
+        ws = ded_workspace_bytes(self.cfg)
+        if ws == 0:
+            raise DedError(DED_EINVAL, "ded_workspace_bytes")
+        L = model_cfg.n_layers
+        with torch.cuda.device(self.device):
+            self.stream = torch.cuda.current_stream()
+            self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.device)
+            kvb = ded_kv_layer_bytes(self.cfg)
+            self.k_cache = [torch.empty(kvb, dtype=torch.uint8, device=self.device) for _ in range(L)]
+            self.v_cache = [torch.empty(kvb, dtype=torch.uint8, device=self.device) for _ in range(L)]
+            dev = lambda a, dt=self.dtype: _to_device(a, self.device, dt)
+            keep = []  # plain weights, alive until init returns
+
+            def cat(parts):
+                ts = [dev(p) for p in parts]
+                t = ts[0] if len(ts) == 1 else torch.cat(ts, dim=0)
+                keep.append(t)
+                return t.data_ptr()
+
+            arr = lambda ptrs: (C.c_void_p * max(len(ptrs), 1))(*ptrs)
+            lw = weights["layers"]
+            W = ded_weights()
+            W.emb, W.lm_head = cat([weights["emb"]]), cat([weights["lm_head"]])
+            fn = dev(weights["final_norm"], "fp32"); keep.append(fn)
+            W.final_norm = fn.data_ptr()
+            a_qkv = arr([cat([l["wq"], l["wk"], l["wv"]]) for l in lw])
+            a_o = arr([cat([l["wo"]]) for l in lw])
+            a_gu = arr([cat([l["wg"], l["wu"]]) for l in lw])
+            a_d = arr([cat([l["wd"]]) for l in lw])
+            na = [dev(l["norm_attn"], "fp32") for l in lw]
+            nf = [dev(l["norm_ffn"], "fp32") for l in lw]
+            keep += na + nf
+            a_na, a_nf = arr([t.data_ptr() for t in na]), arr([t.data_ptr() for t in nf])
+            W.wqkv, W.wo, W.wgate_up, W.wdown, W.norm_attn, W.norm_ffn = a_qkv, a_o, a_gu, a_d, a_na, a_nf
+            KV = ded_kv()
+            a_k, a_v = arr([t.data_ptr() for t in self.k_cache]), arr([t.data_ptr() for t in self.v_cache])
+            KV.k, KV.v = a_k, a_v
+            torch.cuda.synchronize(self.device)
+            self.ctx = ded_verify_init(self.cfg, W, KV, self.workspace.data_ptr(), ws, self.stream.cuda_stream)
+            del keep
+        self._batch = 0
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            ded_verify_free(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- helpers
+    def _pad(self, rows: Sequence[Sequence[int]], fill: int) -> np.ndarray:
+        out = np.full((len(rows), self.max_nodes), fill, np.int32)
+        for b, r in enumerate(rows):
+            out[b, : len(r)] = np.asarray(r, dtype=np.int32)
+        return out
+
+    def verify_step(self, prefix_len, parents, tokens, want_logits=False):
+        """parents / tokens: one sequence of ints per batch entry.  Returns fp32 logits
+        [batch][max_nodes][vocab] (device tensor) when want_logits."""
+        B = len(parents)
+        nn = [len(p) for p in parents]
+        logits = None
+        if want_logits:
+            logits = self.torch.zeros((B, self.max_nodes, self.mc.vocab), dtype=self.torch.float32, device=self.device)
+        rc = ded_verify_step(self.ctx, prefix_len, nn, self._pad(parents, -1), self._pad(tokens, 0),
+                             logits.data_ptr() if want_logits else None)
+        if rc != DED_OK:
+            raise DedError(rc, "ded_verify_step")
+        self._batch = B
+        return logits
+
+    def accept(self, mode=0):
+        rc, acc, nacc, path, newp = ded_accept(self.ctx, mode, self._batch, self.max_nodes)
+        if rc != DED_OK:
+            raise DedError(rc, "ded_accept")
+        return ([acc[b, : nacc[b]].tolist() for b in range(self._batch)],
+                [path[b, : nacc[b]].tolist() for b in range(self._batch)], newp.tolist())
+
+    def get_argmax(self):
+        rc, a, m = ded_get_argmax(self.ctx, self._batch, self.max_nodes)
+        if rc != DED_OK:
+            raise DedError(rc, "ded_get_argmax")
+        return a, m
+
+    def kv_store(self, layer, seq, first_slot, k_plain=None, v_plain=None):
+        """k_plain / v_plain: [Hkv][n][hd] numpy (fp32 or bf16 bits) or device tensors."""
+        kt = None if k_plain is None else _to_device(k_plain, self.device, self.dtype)
+        vt = None if v_plain is None else _to_device(v_plain, self.device, self.dtype)
+        n = (kt if kt is not None else vt).shape[1]
+        rc = ded_kv_store(self.ctx, layer, seq, first_slot, n, kt.data_ptr() if kt is not None else None,
+                          vt.data_ptr() if vt is not None else None)
+        if rc != DED_OK:
+            raise DedError(rc, "ded_kv_store")
+        self.torch.cuda.synchronize(self.device)
+
+    def kv_load(self, layer, seq, first_slot, n):
+        t = self.torch
+        dt = t.bfloat16 if self.dtype == "bf16" else t.float32
+        k = t.empty((self.mc.n_kv_heads, n, self.mc.head_dim), dtype=dt, device=self.device)
+        v = t.empty_like(k)
+        rc = ded_kv_load(self.ctx, layer, seq, first_slot, n, k.data_ptr(), v.data_ptr())
+        if rc != DED_OK:
+            raise DedError(rc, "ded_kv_load")
+        t.cuda.synchronize(self.device)
+        return k, v
+
+    def tree_attention(self, layer, prefix_len, parents, q, k_tree, v_tree):
+        """q [B][max_nodes][H][hd], k_tree / v_tree [B][Hkv][max_nodes][hd] device tensors in storage dtype."""
+        out = self.torch.zeros_like(q)
+        nn = [len(p) for p in parents]
+        rc = ded_tree_attention(self.ctx, layer, prefix_len, nn, self._pad(parents, -1), q.data_ptr(),
+                                k_tree.data_ptr(), v_tree.data_ptr(), out.data_ptr())
+        if rc != DED_OK:
+            raise DedError(rc, "ded_tree_attention")
+        return out
+
+    def profile(self, on: bool):
+        rc = ded_profile_enable(self.ctx, on)
+        if rc != DED_OK:
+            raise DedError(rc, "ded_profile_enable")
+
+    def profile_read(self) -> dict:
+        return ded_profile_read(self.ctx)

@@ -1,0 +1,250 @@
+// Tree-masked attention for the bf16 path (head_dim 128), split over the key axis.
+//
+// Work unit: (sequence, kv head, tile of 64 "virtual rows", key range).  The virtual rows of a kv head
+// are its G query heads x n_step tree rows (vr = g * n_step + node), so grouped-query heads share
+// every K/V byte that is fetched.  A workgroup of 4 wavefronts streams its key range in tiles of 64
+// keys: the K and V^T fragments of a tile (32 KiB, contiguous in the cache) are fetched with fully
+// coalesced 16-byte loads, parked in LDS (double buffered) and consumed by all four wavefronts, each
+// of which owns 16 of the 64 rows:
+//     S^T = K . Q^T           v_mfma_f32_16x16x32_bf16, A = key fragment (LDS), B = query fragment (VGPR)
+//     online soft-max          per lane: 1 row, 16 keys of the tile; row max via two wavefront shuffles
+//     O^T += V^T . P^T         A = value fragment (LDS), B = probabilities straight from the S^T registers
+// The key rows of a 32-key group are interleaved inside the two 16-row tiles (see packk_index) so that
+// after the first product a lane holds 8 consecutive keys - exactly the B-operand slice the second
+// product needs, with no cross-lane traffic.  The ancestor mask is a per-row bitmask over tree slots;
+// tiles that lie entirely inside the prefix skip all mask work.
+// Each workgroup writes (running max, sum, unnormalised output) per row; a second kernel merges the
+// key ranges in a fixed order and writes bf16 output in PackX for the O projection.
+#include <algorithm>
+
+#include "bf16_layout.h"
+#include "ded_kernels.h"
+
+namespace ded {
+
+namespace {
+
+constexpr int TILE = 64;         // keys per tile
+constexpr int TILE_U4 = 1024;    // uint4 units of one K (or V) tile: 64 keys * 128 dims * 2 B / 16
+constexpr float NEG_BIG = -1.0e30f;
+
+__global__ __launch_bounds__(256) void tree_attn_partial_kernel(
+    const uint4* __restrict__ qp, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
+    float* __restrict__ part_o, float2* __restrict__ part_ml, const uint64_t* __restrict__ mask,
+    const int32_t* __restrict__ seq_p, const int32_t* __restrict__ seq_n, int n_step, int H, int Hkv, int cap,
+    int n_splits, float scale_log2e) {
+  __shared__ uint4 lds[2][2 * TILE_U4];  // [buffer][K tile | V tile], 2 x 32 KiB
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int split = blockIdx.x, row_tile = blockIdx.y, bz = blockIdx.z;
+  const int b = bz / Hkv, kvh = bz - b * Hkv;
+  const int G = H / Hkv;
+  const int P = seq_p[b], N = seq_n[b], T = P + N;
+  const int n_tiles = (T + TILE - 1) / TILE;
+  const int t_begin = (int)((int64_t)split * n_tiles / n_splits);
+  const int t_end = (int)((int64_t)(split + 1) * n_tiles / n_splits);
+  const int VR = G * n_step;
+  const int vrb = row_tile * 4 + wave;
+  const bool active = vrb * 16 < VR;  // wavefront owns real rows
+  const int vr = vrb * 16 + (lane & 15);
+  const int quad = lane >> 4;
+  const int g = active ? vr / n_step : 0;
+  const int node = active ? vr - g * n_step : 0;
+  const uint64_t* mrow = mask + ((int64_t)b * n_step + node) * 4;
+
+  bf16x8_t q[4];
+  if (active) {
+    const uint4* qsrc = qp + (((int64_t)bz * (VR / 16) + vrb) * 4 << 6) + lane;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) q[kk] = __builtin_bit_cast(bf16x8_t, qsrc[kk << 6]);
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) q[kk] = __builtin_bit_cast(bf16x8_t, make_uint4(0, 0, 0, 0));
+  }
+
+  const uint4* kbase = kc + (int64_t)bz * cap * 16;  // 16 uint4 per key
+  const uint4* vbase = vc + (int64_t)bz * cap * 16;
+
+  f32x4_t o[8];
+#pragma unroll
+  for (int hb = 0; hb < 8; ++hb) o[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = NEG_BIG, l_run = 0.f;
+
+  uint4 stage[8];
+  auto load_tile = [&](int t) {
+    const uint4* ks = kbase + (int64_t)t * TILE_U4 + tid;
+    const uint4* vs = vbase + (int64_t)t * TILE_U4 + tid;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      stage[i] = ks[i * 256];
+      stage[4 + i] = vs[i * 256];
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      lds[buf][i * 256 + tid] = stage[i];
+      lds[buf][TILE_U4 + i * 256 + tid] = stage[4 + i];
+    }
+  };
+
+  auto compute_tile = [&](int buf, int t) {
+    const uint4* lk = lds[buf];
+    const uint4* lv = lds[buf] + TILE_U4;
+    // S^T: s[kb][c][i] = score of key  t*64 + kb*32 + quad*8 + c*4 + i  against this lane's row
+    f32x4_t s[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          bf16x8_t a = __builtin_bit_cast(bf16x8_t, lk[(((kb * 2 + c) * 4 + kk) << 6) + lane]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, q[kk], acc, 0, 0, 0);
+        }
+        s[kb][c] = acc;
+      }
+    const int key0 = t * TILE;
+    float p[2][8];
+    float mx = NEG_BIG;
+    if (key0 + TILE <= P) {  // whole tile inside the prefix: every key visible
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          p[kb][j] = s[kb][j >> 2][j & 3] * scale_log2e;
+          mx = fmaxf(mx, p[kb][j]);
+        }
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          int key = key0 + kb * 32 + quad * 8 + j;
+          bool vis = key < P;
+          if (!vis && key < T) {
+            int tt = key - P;
+            vis = (mrow[tt >> 6] >> (tt & 63)) & 1ull;
+          }
+          float v = vis ? s[kb][j >> 2][j & 3] * scale_log2e : NEG_BIG;
+          p[kb][j] = v;
+          mx = fmaxf(mx, v);
+        }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    float lsum = 0.f;
+    bf16x8_t pb[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      uint32_t w[4];
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        float e0 = p[kb][j] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[kb][j] - m_new) : 0.f;
+        float e1 = p[kb][j + 1] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[kb][j + 1] - m_new) : 0.f;
+        uint16_t h0 = f32_to_bf16(e0), h1 = f32_to_bf16(e1);
+        lsum += bf16_to_f32(h0) + bf16_to_f32(h1);  // the sum uses the rounded weights the product uses
+        w[j >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      }
+      pb[kb] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+    l_run = l_run * alpha + lsum;
+    m_run = m_new;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int hb = 0; hb < 8; ++hb) o[hb] *= alpha;
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int hb = 0; hb < 8; ++hb) {
+        bf16x8_t a = __builtin_bit_cast(bf16x8_t, lv[((kb * 8 + hb) << 6) + lane]);
+        o[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[kb], o[hb], 0, 0, 0);
+      }
+  };
+
+  if (t_begin < t_end) {
+    load_tile(t_begin);
+    store_tile(0);
+    __syncthreads();
+    int buf = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+      const bool more = t + 1 < t_end;
+      if (more) load_tile(t + 1);
+      if (active) compute_tile(buf, t);
+      if (more) store_tile(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  if (active) {
+    float l = l_run;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int h = kvh * G + g;
+    const int64_t prow = (((int64_t)b * H + h) * n_splits + split) * n_step + node;
+    float* po = part_o + prow * 128 + quad * 4;
+#pragma unroll
+    for (int hb = 0; hb < 8; ++hb)
+      *reinterpret_cast<float4*>(po + hb * 16) = make_float4(o[hb][0], o[hb][1], o[hb][2], o[hb][3]);
+    if (quad == 0) part_ml[prow] = make_float2(m_run, l);
+  }
+}
+
+// One workgroup of 128 threads per (row, query head): thread = head dim.
+__global__ __launch_bounds__(128) void tree_attn_merge_kernel(bf16_t* __restrict__ op, int RB,
+                                                              const float* __restrict__ part_o,
+                                                              const float2* __restrict__ part_ml, int n_splits,
+                                                              int n_step, int H) {
+  const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+  const int b = r / n_step, node = r - b * n_step;
+  const int64_t base = (((int64_t)b * H + h) * n_splits) * n_step + node;
+  float M = NEG_BIG;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[base + (int64_t)s * n_step].x);
+  float L = 0.f, acc = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    float2 ml = part_ml[base + (int64_t)s * n_step];
+    float w = __builtin_amdgcn_exp2f(ml.x - M);
+    L += ml.y * w;
+    acc += part_o[(base + (int64_t)s * n_step) * 128 + i] * w;
+  }
+  op[packx_index(r, h * 128 + i, RB)] = f32_to_bf16(acc / L);
+}
+
+}  // namespace
+
+int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int64_t part_rows_cap) {
+  const int G = md.H / md.Hkv;
+  const int row_tiles = (G * m.n_step + 63) / 64;
+  const int tiles = (max_p + m.n_step + TILE - 1) / TILE;
+  const int base = m.batch * md.Hkv * row_tiles;
+  int ns = std::max(1, 512 / std::max(base, 1));
+  ns = std::min(ns, std::max(1, tiles / 4));  // keep >= 4 tiles (256 keys) per range
+  while (ns > 1 && (int64_t)m.batch * md.H * ns * m.n_step > part_rows_cap) --ns;
+  return ns;
+}
+
+void bf16_tree_attention_partial(const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc, float* part_o,
+                                 float2* part_ml, int n_splits, const StepMeta& m, const ModelDims& md,
+                                 hipStream_t s) {
+  if (md.hd != 128 || n_splits < 1 || m.rows <= 0) return;
+  const int G = md.H / md.Hkv;
+  const int row_tiles = (G * m.n_step + 63) / 64;
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)md.hd);
+  hipLaunchKernelGGL(tree_attn_partial_kernel, dim3(n_splits, row_tiles, m.batch * md.Hkv), dim3(256), 0, s,
+                     reinterpret_cast<const uint4*>(q_packed), reinterpret_cast<const uint4*>(kc),
+                     reinterpret_cast<const uint4*>(vc), part_o, part_ml, m.mask, m.seq_p, m.seq_n, m.n_step, md.H,
+                     md.Hkv, md.cap, n_splits, scale_log2e);
+}
+
+void bf16_tree_attention_merge(bf16_t* o_packed, int rows_pad, const float* part_o, const float2* part_ml,
+                               int n_splits, const StepMeta& m, const ModelDims& md, hipStream_t s) {
+  if (m.rows <= 0) return;
+  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(m.rows, md.H), dim3(128), 0, s, o_packed, rows_pad / 16, part_o,
+                     part_ml, n_splits, m.n_step, md.H);
+}
+
+}  // namespace ded

@@ -1,0 +1,109 @@
+// Internal launcher interface between the host scheduler (ded_api.hip) and the kernel files.
+// Every launcher enqueues on the given stream and checks its shapes on the host first; the
+// kernels themselves assume those shapes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ded {
+
+// Device-resident description of the current step (one verification forward).
+// Row r = b * n_step + node; n_step = the step's padded tree size (multiple of 16).
+struct StepMeta {
+  const int32_t* token;   // [R]   token id of the row (padding rows repeat the root token)
+  const int32_t* parent;  // [R]   parent node index inside the sequence, -1 for root / padding
+  const int32_t* depth;   // [R]
+  const int32_t* pos;     // [R]   absolute position prefix_len + depth
+  const uint64_t* mask;   // [R][4] ancestor-or-self bitmask over node indices (bit j = node j)
+  const int32_t* seq_p;   // [B]   prefix_len per sequence
+  const int32_t* seq_n;   // [B]   real tree rows per sequence
+  int32_t batch, n_step, rows;  // rows = batch * n_step
+};
+
+struct ModelDims {
+  int32_t n_layers, d, H, Hkv, hd, F, V, cap;
+  float rope_base, eps;
+};
+
+// ---- shared (both dtypes) --------------------------------------------------------------
+// cos/sin of pos[r] * base^(-2i/hd), i < hd/2, angles formed in fp64.  tab: [R][hd/2] float2.
+void launch_rope_table(float2* tab, const int32_t* pos, int rows, int hd, float base, hipStream_t s);
+// Per-row argmax (lowest index on exact ties) and top-1 minus top-2 over V fp32 logits.
+void launch_argmax(const float* logits, int64_t row_stride, int rows, int V, int32_t* amax,
+                   float* margin, hipStream_t s);
+// Copy rows of real nodes to the caller's [batch][max_nodes][V] logits buffer.
+void launch_export_logits(float* dst, const float* src, int64_t src_stride, const StepMeta& m,
+                          int max_nodes, int V, hipStream_t s);
+// Approval walk (one wavefront per sequence).  mode 0 greedy, mode 1 keep the whole chain.
+// out_n [B], out_path / out_tok [B][stride].
+void launch_accept_walk(const StepMeta& m, const int32_t* amax, int mode, int32_t* out_n,
+                        int32_t* out_path, int32_t* out_tok, int stride, hipStream_t s);
+
+// ---- fp32 path (plain row-major everywhere; cache [B][Hkv][cap][hd]) ---------------------
+void f32_embed(float* x, const float* emb, const StepMeta& m, int d, hipStream_t s);
+void f32_rmsnorm(float* y, const float* x, const float* gain, int rows, int d, float eps, hipStream_t s);
+// Y[r][n] (+)= sum_k X[r][k] W[n][k]
+void f32_gemm(float* Y, const float* X, const float* W, int rows, int N, int K, bool accumulate, hipStream_t s);
+void f32_rope_kv(float* qkv, float* kc, float* vc, const float2* tab, const StepMeta& m,
+                 const ModelDims& md, hipStream_t s);
+void f32_tree_attention(float* o, const float* qkv, int q_stride, const float* kc, const float* vc,
+                        const StepMeta& m, const ModelDims& md, hipStream_t s);
+void f32_silu_mul(float* h, const float* gu, int rows, int F, hipStream_t s);
+void f32_kv_compact(float* const* kc, float* const* vc, const int32_t* path, const int32_t* n_acc,
+                    const StepMeta& m, const ModelDims& md, int stride, hipStream_t s);
+// plain [Hkv][n][hd] <-> cache
+void f32_kv_copy(float* cache, float* plain, bool to_cache, int seq, int first, int n,
+                 const ModelDims& md, hipStream_t s);
+void f32_scatter_tree_kv(float* kc, float* vc, const float* k_tree, const float* v_tree,
+                         const StepMeta& m, const ModelDims& md, int max_nodes, hipStream_t s);
+// q [B][max_nodes][H][hd] -> qkv-style rows [R][H*hd]; and back for the output
+void f32_gather_rows(float* dst, const float* src, const StepMeta& m, int max_nodes, int width,
+                     bool to_padded, hipStream_t s);
+
+// ---- bf16 path ---------------------------------------------------------------------------
+// Operand-fragment layouts (units: bf16 elements; a fragment = 64 lanes x 8 elements = 1 KiB):
+//  PackW  W[N][K]   : frag (nt = n/16, kt = k/32) at nt*(K/32)+kt; lane = ((k%32)/8)*16 + n%16; elem k%8
+//  PackX  X[R][K]   : frag (kt, rb = r/16) at kt*RB+rb;            lane = ((k%32)/8)*16 + r%16; elem k%8
+//  PackQ  per (b,kvh): frag (vrb, kk = hd/32) at vrb*4+kk, virtual row vr = g*n_step + node
+//  PackK  per (b,kvh): 32-key group kb; frag (kb, c, kk) at (kb*2+c)*4+kk; key%32 = q8*8 + c*4 + i
+//                      -> lane = ((hdim%32)/8)*16 + q8*4 + i; elem hdim%8
+//  PackVt per (b,kvh): frag (kb, hb = hdim/16) at kb*8+hb; lane = ((key%32)/8)*16 + hdim%16; elem key%8
+typedef uint16_t bf16_t;
+
+void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, hipStream_t s);
+void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream_t s);
+// x[r] += sum_s part[s][r] (n_part may be 0); y = PackX(bf16(rmsnorm(x) * gain))
+void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
+                      const float* gain, int rows, int rows_pad, int d, float eps, hipStream_t s);
+// Skinny GEMM on the matrix cores: part[s][r][n] = sum_{k in slice s} X[r][k] W[n][k], fp32.
+// rows_pad % 64 == 0, N % 16 == 0, K % 128 == 0, 1 <= splits <= K/128.
+void bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed,
+               int rows_pad, int N, int K, int splits, int64_t out_row_stride, hipStream_t s);
+int bf16_gemm_pick_splits(int rows_pad, int N, int K);
+// sum partials, rotate q/k, write PackQ and the cache fragments
+void bf16_qkv_epilogue(const float* part, int n_part, int64_t part_stride, bf16_t* q_packed,
+                       bf16_t* kc, bf16_t* vc, const float2* tab, const StepMeta& m,
+                       const ModelDims& md, hipStream_t s);
+// Tree-masked attention, two launches: split-KV partials (running max, sum, unnormalised output per
+// key range), then the merge that writes PackX(o).  n_splits from bf16_attn_pick_splits.
+// part_o: [B][H][n_splits][n_step][hd] fp32, part_ml: [B][H][n_splits][n_step] float2 (max, sum).
+int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int64_t part_rows_cap);
+void bf16_tree_attention_partial(const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc, float* part_o,
+                                 float2* part_ml, int n_splits, const StepMeta& m, const ModelDims& md,
+                                 hipStream_t s);
+void bf16_tree_attention_merge(bf16_t* o_packed, int rows_pad, const float* part_o, const float2* part_ml,
+                               int n_splits, const StepMeta& m, const ModelDims& md, hipStream_t s);
+void bf16_silu_mul(bf16_t* h_packed, const float* part, int n_part, int64_t part_stride, int rows,
+                   int rows_pad, int F, hipStream_t s);
+void bf16_kv_compact(bf16_t* const* kc, bf16_t* const* vc, const int32_t* path, const int32_t* n_acc,
+                     const StepMeta& m, const ModelDims& md, int stride, hipStream_t s);
+void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_plain, bool to_cache,
+                  int seq, int first, int n, const ModelDims& md, hipStream_t s);
+void bf16_scatter_tree_kv(bf16_t* kc, bf16_t* vc, const bf16_t* k_tree, const bf16_t* v_tree,
+                          const StepMeta& m, const ModelDims& md, int max_nodes, hipStream_t s);
+void bf16_pack_q(bf16_t* q_packed, const bf16_t* q_plain, const StepMeta& m, const ModelDims& md,
+                 int max_nodes, hipStream_t s);
+void bf16_unpack_o(bf16_t* out_plain, const bf16_t* o_packed, int rows_pad, const StepMeta& m,
+                   const ModelDims& md, int max_nodes, hipStream_t s);
+
+}  // namespace ded

@@ -1,0 +1,320 @@
+// bf16 path, everything that is not a contraction: weight re-layout, embedding gather, residual add +
+// RMSNorm, the QKV epilogue (split-K sum, rotary embedding, cache append), SiLU*up, cache compaction
+// and the plain <-> fragment layout conversions.
+#include <algorithm>
+
+#include "bf16_layout.h"
+#include "ded_kernels.h"
+
+namespace ded {
+
+namespace {
+
+__device__ inline float wave_sum(float v) {
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+__device__ inline float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+struct F8 {
+  float v[8];
+};
+__device__ inline F8 load8(const float* p) {
+  F8 r;
+  float4 a = *reinterpret_cast<const float4*>(p);
+  float4 b = *reinterpret_cast<const float4*>(p + 4);
+  r.v[0] = a.x; r.v[1] = a.y; r.v[2] = a.z; r.v[3] = a.w;
+  r.v[4] = b.x; r.v[5] = b.y; r.v[6] = b.z; r.v[7] = b.w;
+  return r;
+}
+__device__ inline void store8(float* p, const F8& r) {
+  *reinterpret_cast<float4*>(p) = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(r.v[4], r.v[5], r.v[6], r.v[7]);
+}
+__device__ inline uint4 to_bf16x8(const F8& r) {
+  return make_uint4(pack2_bf16(r.v[0], r.v[1]), pack2_bf16(r.v[2], r.v[3]), pack2_bf16(r.v[4], r.v[5]),
+                    pack2_bf16(r.v[6], r.v[7]));
+}
+// sum over split-K slices in slice order (fixed order -> deterministic)
+__device__ inline F8 sum_parts8(const float* part, int n_part, int64_t part_stride, int64_t off) {
+  F8 acc = load8(part + off);
+  for (int s = 1; s < n_part; ++s) {
+    F8 t = load8(part + (int64_t)s * part_stride + off);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc.v[i] += t.v[i];
+  }
+  return acc;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+__global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K) {
+  int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // destination 16-byte unit
+  int64_t total = (int64_t)N * K / 8;
+  if (u >= total) return;
+  int lane = (int)(u & 63);
+  int64_t frag = u >> 6;
+  int KT = K >> 5;
+  int nt = (int)(frag / KT), kt = (int)(frag - (int64_t)nt * KT);
+  int n = nt * 16 + (lane & 15);
+  int k = kt * 32 + (lane >> 4) * 8;
+  dst[u] = *reinterpret_cast<const uint4*>(src + (int64_t)n * K + k);
+}
+void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, hipStream_t s) {
+  int64_t units = (int64_t)N * K / 8;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
+                     reinterpret_cast<uint4*>(dst), src, N, K);
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void bf16_embed_kernel(float* __restrict__ x, const bf16_t* __restrict__ emb,
+                                  const int32_t* __restrict__ token, int d) {
+  int r = blockIdx.x;
+  const bf16_t* src = emb + (int64_t)token[r] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) x[(int64_t)r * d + i] = bf16_to_f32(src[i]);
+}
+void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream_t s) {
+  hipLaunchKernelGGL(bf16_embed_kernel, dim3(m.rows), dim3(256), 0, s, x, emb, m.token, d);
+}
+
+// ------------------------------------------------------------------------------------------
+// x[r] += sum of the pending split-K slices; y = bf16(x * rsqrt(mean(x^2) + eps) * gain) in PackX.
+__global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part,
+                                                          int n_part, int64_t part_stride, uint4* __restrict__ y,
+                                                          const float* __restrict__ gain, int RB, int d, float eps) {
+  __shared__ float sh[4];
+  int r = blockIdx.x;
+  float* xr = x + (int64_t)r * d;
+  float ss = 0.f;
+  for (int u = threadIdx.x; u < d / 8; u += 256) {
+    F8 v = load8(xr + u * 8);
+    if (n_part > 0) {
+      F8 p = sum_parts8(part, n_part, part_stride, (int64_t)r * d + u * 8);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v.v[i] += p.v[i];
+      store8(xr + u * 8, v);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss += v.v[i] * v.v[i];
+  }
+  ss = block_sum_256(ss, sh);  // the barriers inside also order the x stores before the reads below
+  float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int u = threadIdx.x; u < d / 8; u += 256) {
+    F8 v = load8(xr + u * 8);
+    F8 g = load8(gain + u * 8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v.v[i] = v.v[i] * inv * g.v[i];
+    y[packx_index(r, u * 8, RB) >> 3] = to_bf16x8(v);
+  }
+}
+void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
+                      const float* gain, int rows, int rows_pad, int d, float eps, hipStream_t s) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(add_rmsnorm_kernel, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
+                     reinterpret_cast<uint4*>(y_packed), gain, rows_pad / 16, d, eps);
+}
+
+// ------------------------------------------------------------------------------------------
+// QKV epilogue.  One thread owns 8 head dims i0..i0+7 of the first half of a head and their rotary
+// partners i0+64..i0+71.  Query heads go to PackQ, key heads (rotated) and value heads of real nodes
+// go to the cache fragments at slot prefix_len + node.
+__global__ __launch_bounds__(256) void qkv_epilogue_kernel(
+    const float* __restrict__ part, int n_part, int64_t part_stride, bf16_t* __restrict__ qp,
+    bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, const float2* __restrict__ tab,
+    const int32_t* __restrict__ seq_p, const int32_t* __restrict__ seq_n, int n_step, int H, int Hkv, int cap) {
+  const int hd = 128, half = 64;
+  int r = blockIdx.x;
+  int b = r / n_step, node = r - b * n_step;
+  int G = H / Hkv;
+  int width = (H + 2 * Hkv) * hd;
+  bool real = node < seq_n[b];
+  int slot = seq_p[b] + node;
+  int units = (H + 2 * Hkv) * 8;
+  for (int u = blockIdx.y * 256 + threadIdx.x; u < units; u += gridDim.y * 256) {
+    int hs = u >> 3, i0 = (u & 7) * 8;
+    if (hs >= H && !real) continue;
+    int64_t off = (int64_t)r * width + (int64_t)hs * hd + i0;
+    F8 a = sum_parts8(part, n_part, part_stride, off);
+    F8 c = sum_parts8(part, n_part, part_stride, off + half);
+    if (hs < H + Hkv) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float2 cs = tab[(int64_t)r * half + i0 + i];
+        float ra = a.v[i] * cs.x - c.v[i] * cs.y;
+        float rc = c.v[i] * cs.x + a.v[i] * cs.y;
+        a.v[i] = ra;
+        c.v[i] = rc;
+      }
+    }
+    uint4 lo = to_bf16x8(a), hi = to_bf16x8(c);
+    if (hs < H) {
+      int kvh = hs / G, g = hs - kvh * G;
+      int vr = g * n_step + node;
+      bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd);
+      *reinterpret_cast<uint4*>(base + packq_index(vr, i0)) = lo;
+      *reinterpret_cast<uint4*>(base + packq_index(vr, i0 + half)) = hi;
+    } else if (hs < H + Hkv) {
+      bf16_t* base = kc + ((int64_t)b * Hkv + (hs - H)) * ((int64_t)cap * hd);
+      *reinterpret_cast<uint4*>(base + packk_index(slot, i0)) = lo;
+      *reinterpret_cast<uint4*>(base + packk_index(slot, i0 + half)) = hi;
+    } else {
+      bf16_t* base = vc + ((int64_t)b * Hkv + (hs - H - Hkv)) * ((int64_t)cap * hd);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        base[packvt_index(slot, i0 + i)] = f32_to_bf16(a.v[i]);
+        base[packvt_index(slot, i0 + half + i)] = f32_to_bf16(c.v[i]);
+      }
+    }
+  }
+}
+void bf16_qkv_epilogue(const float* part, int n_part, int64_t part_stride, bf16_t* q_packed, bf16_t* kc,
+                       bf16_t* vc, const float2* tab, const StepMeta& m, const ModelDims& md, hipStream_t s) {
+  int units = (md.H + 2 * md.Hkv) * 8;
+  int gy = std::min(8, (units + 255) / 256);
+  hipLaunchKernelGGL(qkv_epilogue_kernel, dim3(m.rows, gy), dim3(256), 0, s, part, n_part, part_stride, q_packed,
+                     kc, vc, tab, m.seq_p, m.seq_n, m.n_step, md.H, md.Hkv, md.cap);
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void silu_mul_kernel(uint4* __restrict__ h, const float* __restrict__ part, int n_part,
+                                int64_t part_stride, int RB, int F) {
+  int r = blockIdx.y;
+  int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= F / 8) return;
+  int64_t off = (int64_t)r * 2 * F + u * 8;
+  F8 g = sum_parts8(part, n_part, part_stride, off);
+  F8 up = sum_parts8(part, n_part, part_stride, off + F);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) g.v[i] = g.v[i] / (1.0f + __expf(-g.v[i])) * up.v[i];
+  h[packx_index(r, u * 8, RB) >> 3] = to_bf16x8(g);
+}
+void bf16_silu_mul(bf16_t* h_packed, const float* part, int n_part, int64_t part_stride, int rows, int rows_pad,
+                   int F, hipStream_t s) {
+  if (rows <= 0 || F <= 0) return;
+  hipLaunchKernelGGL(silu_mul_kernel, dim3((F / 8 + 255) / 256, rows), dim3(256), 0, s,
+                     reinterpret_cast<uint4*>(h_packed), part, n_part, part_stride, rows_pad / 16, F);
+}
+
+// ------------------------------------------------------------------------------------------
+// Compaction in the fragment layouts.  Threads 0..15 move the sixteen 16-byte key units of a slot,
+// threads 16..143 one value element each; every thread walks the path upwards (see the fp32 kernel).
+__global__ __launch_bounds__(192) void bf16_kv_compact_kernel(bf16_t* const* __restrict__ kc,
+                                                              bf16_t* const* __restrict__ vc,
+                                                              const int32_t* __restrict__ path,
+                                                              const int32_t* __restrict__ n_acc,
+                                                              const int32_t* __restrict__ seq_p, int Hkv, int cap,
+                                                              int stride) {
+  const int hd = 128;
+  int layer = blockIdx.x, bh = blockIdx.y;
+  int b = bh / Hkv;
+  int len = n_acc[b], P = seq_p[b];
+  const int32_t* pth = path + (int64_t)b * stride;
+  int t = threadIdx.x;
+  if (t < 16) {
+    bf16_t* K = kc[layer] + (int64_t)bh * cap * hd;
+    for (int j = 0; j < len; ++j) {
+      int src = pth[j];
+      if (src != j)
+        *reinterpret_cast<uint4*>(K + packk_index(P + j, t * 8)) =
+            *reinterpret_cast<const uint4*>(K + packk_index(P + src, t * 8));
+    }
+  } else if (t < 16 + hd) {
+    bf16_t* V = vc[layer] + (int64_t)bh * cap * hd;
+    int hdim = t - 16;
+    for (int j = 0; j < len; ++j) {
+      int src = pth[j];
+      if (src != j) V[packvt_index(P + j, hdim)] = V[packvt_index(P + src, hdim)];
+    }
+  }
+}
+void bf16_kv_compact(bf16_t* const* kc, bf16_t* const* vc, const int32_t* path, const int32_t* n_acc,
+                     const StepMeta& m, const ModelDims& md, int stride, hipStream_t s) {
+  hipLaunchKernelGGL(bf16_kv_compact_kernel, dim3(md.n_layers, m.batch * md.Hkv), dim3(192), 0, s, kc, vc, path,
+                     n_acc, m.seq_p, md.Hkv, md.cap, stride);
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void bf16_kv_copy_kernel(bf16_t* __restrict__ kcache, bf16_t* __restrict__ vcache,
+                                    bf16_t* __restrict__ kp, bf16_t* __restrict__ vp, int to_cache, int seq,
+                                    int first, int n, int Hkv, int cap) {
+  const int hd = 128;
+  int j = blockIdx.x, g = blockIdx.y, i = threadIdx.x;
+  int64_t cbase = ((int64_t)seq * Hkv + g) * cap * hd;
+  int64_t pidx = ((int64_t)g * n + j) * hd + i;
+  int64_t ki = cbase + packk_index(first + j, i), vi = cbase + packvt_index(first + j, i);
+  if (to_cache) {
+    if (kp) kcache[ki] = kp[pidx];
+    if (vp) vcache[vi] = vp[pidx];
+  } else {
+    if (kp) kp[pidx] = kcache[ki];
+    if (vp) vp[pidx] = vcache[vi];
+  }
+}
+void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_plain, bool to_cache, int seq,
+                  int first, int n, const ModelDims& md, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(bf16_kv_copy_kernel, dim3(n, md.Hkv), dim3(128), 0, s, kcache, vcache, k_plain, v_plain,
+                     to_cache ? 1 : 0, seq, first, n, md.Hkv, md.cap);
+}
+
+__global__ void bf16_scatter_tree_kv_kernel(bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+                                            const bf16_t* __restrict__ kt, const bf16_t* __restrict__ vt,
+                                            const int32_t* __restrict__ seq_p, const int32_t* __restrict__ seq_n,
+                                            int Hkv, int cap, int max_nodes) {
+  const int hd = 128;
+  int node = blockIdx.x, bh = blockIdx.y, i = threadIdx.x;
+  int b = bh / Hkv;
+  if (node >= seq_n[b]) return;
+  int64_t src = ((int64_t)bh * max_nodes + node) * hd + i;
+  int64_t cbase = (int64_t)bh * cap * hd;
+  int slot = seq_p[b] + node;
+  kc[cbase + packk_index(slot, i)] = kt[src];
+  vc[cbase + packvt_index(slot, i)] = vt[src];
+}
+void bf16_scatter_tree_kv(bf16_t* kc, bf16_t* vc, const bf16_t* k_tree, const bf16_t* v_tree, const StepMeta& m,
+                          const ModelDims& md, int max_nodes, hipStream_t s) {
+  hipLaunchKernelGGL(bf16_scatter_tree_kv_kernel, dim3(max_nodes, m.batch * md.Hkv), dim3(128), 0, s, kc, vc,
+                     k_tree, v_tree, m.seq_p, m.seq_n, md.Hkv, md.cap, max_nodes);
+}
+
+// q plain [B][max_nodes][H][hd] -> PackQ (rows of absent nodes become zero)
+__global__ void bf16_pack_q_kernel(bf16_t* __restrict__ qp, const bf16_t* __restrict__ q,
+                                   const int32_t* __restrict__ seq_n, int n_step, int H, int Hkv, int max_nodes) {
+  const int hd = 128;
+  int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+  int b = r / n_step, node = r - b * n_step;
+  int G = H / Hkv, kvh = h / G, g = h - kvh * G;
+  bf16_t v = 0;
+  if (node < seq_n[b]) v = q[(((int64_t)b * max_nodes + node) * H + h) * hd + i];
+  bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd);
+  base[packq_index(g * n_step + node, i)] = v;
+}
+void bf16_pack_q(bf16_t* q_packed, const bf16_t* q_plain, const StepMeta& m, const ModelDims& md, int max_nodes,
+                 hipStream_t s) {
+  hipLaunchKernelGGL(bf16_pack_q_kernel, dim3(m.rows, md.H), dim3(128), 0, s, q_packed, q_plain, m.seq_n, m.n_step,
+                     md.H, md.Hkv, max_nodes);
+}
+
+// PackX(o) [rows_pad][H*hd] -> plain [B][max_nodes][H][hd]
+__global__ void bf16_unpack_o_kernel(bf16_t* __restrict__ out, const bf16_t* __restrict__ op,
+                                     const int32_t* __restrict__ seq_n, int n_step, int H, int RB, int max_nodes) {
+  const int hd = 128;
+  int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+  int b = r / n_step, node = r - b * n_step;
+  if (node >= seq_n[b]) return;
+  out[(((int64_t)b * max_nodes + node) * H + h) * hd + i] = op[packx_index(r, h * hd + i, RB)];
+}
+void bf16_unpack_o(bf16_t* out_plain, const bf16_t* o_packed, int rows_pad, const StepMeta& m, const ModelDims& md,
+                   int max_nodes, hipStream_t s) {
+  hipLaunchKernelGGL(bf16_unpack_o_kernel, dim3(m.rows, md.H), dim3(128), 0, s, out_plain, o_packed, m.seq_n,
+                     m.n_step, md.H, rows_pad / 16, max_nodes);
+}
+
+}  // namespace ded

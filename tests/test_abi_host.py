@@ -1,0 +1,90 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares, and the
+argument validation (which runs before any launch) returns the documented codes.  No GPU calls."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2407_12021_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2407_12021_amd.build import build_library
+        build_library()
+    return binding
+
+
+def test_every_declared_symbol_is_exported(b):
+    header = open(os.path.join(ROOT, "include", "ded_verify.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ded_[a-z_0-9]+)\s*\(", header))
+    assert {"ded_verify_init", "ded_verify_step", "ded_accept"} <= declared
+    L = b.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(b.EXPORTS)
+
+
+def _cfg(b, **kw):
+    base = dict(n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688, vocab=4096,
+                rope_base=10000.0, rms_eps=1e-5, dtype="fp32", max_batch=2, kv_capacity=144, max_nodes=16)
+    base.update(kw)
+    return b.make_config(**base)
+
+
+def test_config_validation_and_sizes(b):
+    assert b.ded_workspace_bytes(_cfg(b)) > 0
+    assert b.ded_kv_layer_bytes(_cfg(b)) == 2 * 4 * 144 * 64 * 4
+    for bad in (dict(n_heads=3, n_kv_heads=2), dict(max_nodes=257), dict(head_dim=63), dict(dtype=7),
+                dict(dtype="bf16"), dict(vocab=0), dict(rope_base=0.0), dict(max_batch=0)):
+        assert b.ded_workspace_bytes(_cfg(b, **bad)) == 0, bad
+    ok16 = dict(dtype="bf16", head_dim=128, d_model=256, d_ffn=384, vocab=4096, kv_capacity=192)
+    assert b.ded_workspace_bytes(_cfg(b, **ok16)) > 0
+    assert b.ded_kv_layer_bytes(_cfg(b, **ok16)) == 2 * 4 * 192 * 128 * 2
+    for bad in (dict(kv_capacity=100), dict(d_ffn=400), dict(vocab=4100), dict(d_model=192)):
+        assert b.ded_workspace_bytes(_cfg(b, **{**ok16, **bad})) == 0, bad
+
+
+def test_step_validation_codes(b):
+    cfg = _cfg(b)
+    par = np.full((2, 16), -1, np.int32)
+    tok = np.zeros((2, 16), np.int32)
+    par[:, 1:4] = [0, 0, 1]
+    V = b.ded_validate_tree
+    assert V(cfg, [10, 20], [4, 4], par, tok) == b.DED_OK
+    assert V(cfg, [10], [1], par[:1], tok[:1]) == b.DED_OK
+    assert V(cfg, [10, 20, 30], [4, 4, 4], np.tile(par[:1], (3, 1)), np.tile(tok[:1], (3, 1))) == b.DED_EINVAL
+    assert V(cfg, [10, 20], [0, 4], par, tok) == b.DED_EINVAL
+    assert V(cfg, [10, 20], [17, 4], par, tok) == b.DED_EINVAL
+    assert V(cfg, [-1, 20], [4, 4], par, tok) == b.DED_EINVAL
+    assert V(cfg, [141, 20], [4, 4], par, tok) == b.DED_ECAP
+    assert V(cfg, [140, 20], [4, 4], par, tok) == b.DED_OK
+    assert V(cfg, [10, 20], [4, 4], None, tok) == b.DED_EINVAL
+    bad = par.copy(); bad[1, 0] = 0
+    assert V(cfg, [10, 20], [4, 4], bad, tok) == b.DED_ETREE
+    bad = par.copy(); bad[0, 2] = 2
+    assert V(cfg, [10, 20], [4, 4], bad, tok) == b.DED_ETREE
+    bad = par.copy(); bad[0, 3] = -1
+    assert V(cfg, [10, 20], [4, 4], bad, tok) == b.DED_ETREE
+    bad = par.copy(); bad[0, 9] = 55  # beyond n_nodes: ignored
+    assert V(cfg, [10, 20], [4, 4], bad, tok) == b.DED_OK
+    t = tok.copy(); t[1, 3] = 4096
+    assert V(cfg, [10, 20], [4, 4], par, t) == b.DED_ETOKEN
+    t = tok.copy(); t[1, 3] = -5
+    assert V(cfg, [10, 20], [4, 4], par, t) == b.DED_ETOKEN
+
+
+def test_init_rejects_bad_arguments_before_touching_the_device(b):
+    with pytest.raises(b.DedError) as e:
+        b.ded_verify_init(_cfg(b, max_nodes=300), None, None, 0, 0, None)
+    assert e.value.code == b.DED_EINVAL
+    with pytest.raises(b.DedError) as e:
+        b.ded_verify_init(_cfg(b), None, None, 0, 0, None)
+    assert e.value.code == b.DED_EINVAL
+    assert b.lib().ded_accept(None, 0, None, None, None, None) == b.DED_EINVAL
+    assert b.lib().ded_verify_step(None, 1, None, None, None, None, None) == b.DED_EINVAL
+    assert "tree" in b.ded_strerror(b.DED_ETREE)
