@@ -148,7 +148,7 @@ def test_lossless_multi_step_decode(dtype):
     Drafts are random except for a planted branch; compared token by token while margins allow."""
     hd = 128 if dtype == "bf16" else 32
     cfg = di.ModelConfig("loss-" + dtype, 2, 128, 2, 2, hd, 256, 512, dtype=dtype)
-    w = di.make_weights(cfg, seed=12, gain_jitter=0.1, std=0.05)
+    w = di.make_weights(cfg, seed=13, gain_jitter=0.1, std=0.3)  # seed / std chosen for wide oracle margins
     prompt = di.zipf_tokens(cfg.vocab, 9, seed=13).tolist()
     n_new = 24
     # oracle AR with margins
@@ -180,7 +180,7 @@ def test_lossless_multi_step_decode(dtype):
         step += 1
     first_unsure = next((i for i, mg in enumerate(margins) if mg <= MARGIN), n_new)
     assert produced[:first_unsure] == ar[:first_unsure]
-    assert first_unsure >= 4, "test model too flat to say anything"
+    assert first_unsure >= 12, "test model too flat to say anything"
     ver.close()
 
 
