@@ -127,13 +127,34 @@ def _stream_id(*parts: int) -> int:
 
 
 def normal_matrix(seed: int, stream: int, shape: Sequence[int], std: float, dtype: str) -> np.ndarray:
-    """i.i.d. N(0, std) drawn in fp32; dtype 'bf16' -> uint16 bit patterns (one RNE rounding)."""
+    """i.i.d. N(0, std) drawn in fp32 (one Philox stream per matrix, filled in 1 Mi-element blocks);
+    dtype 'bf16' -> uint16 bit patterns (one RNE rounding)."""
     g = _rng(seed, stream)
-    a = g.standard_normal(size=tuple(shape), dtype=np.float32)
-    a *= np.float32(std)
-    if dtype == "bf16":
-        return f32_to_bf16_bits(a)
-    return a
+    n = int(np.prod(shape))
+    blk = 1 << 20
+    if dtype != "bf16":
+        out = np.empty(n, np.float32)
+        for s in range(0, n, blk):
+            f = out[s:min(s + blk, n)]
+            g.standard_normal(out=f, dtype=np.float32)
+            f *= np.float32(std)
+        return out.reshape(tuple(shape))
+    out = np.empty(n, np.uint16)
+    buf = np.empty(blk, np.float32)
+    tmp = np.empty(blk, np.uint32)
+    for s in range(0, n, blk):
+        e = min(s + blk, n)
+        f, t = buf[: e - s], tmp[: e - s]
+        g.standard_normal(out=f, dtype=np.float32)
+        f *= np.float32(std)
+        u = f.view(np.uint32)  # round to nearest even on the bit pattern
+        np.right_shift(u, 16, out=t)
+        t &= 1
+        t += 0x7FFF
+        t += u
+        t >>= 16
+        out[s:e] = t
+    return out.reshape(tuple(shape))
 
 
 # --------------------------------------------------------------------------------------
@@ -168,19 +189,24 @@ def make_weights(cfg: ModelConfig, seed: int = 0, gain_jitter: float = 0.0, std:
             g += _rng(seed, stream).standard_normal(cfg.d_model, dtype=np.float32) * np.float32(gain_jitter)
         return g
 
-    def layer(li):
-        out = {}
-        for mi, name in enumerate(_LAYER_MATS):
-            out[name] = normal_matrix(seed, _stream_id(1, li, mi), shapes[name], std, cfg.dtype)
-        out["norm_attn"] = gain(_stream_id(2, li, 0))
-        out["norm_ffn"] = gain(_stream_id(2, li, 1))
-        return out
+    jobs = [(li, mi, name) for li in range(cfg.n_layers) for mi, name in enumerate(_LAYER_MATS)]
+
+    def draw(job):
+        li, mi, name = job
+        return normal_matrix(seed, _stream_id(1, li, mi), shapes[name], std, cfg.dtype)
 
     with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
-        layers = list(ex.map(layer, range(cfg.n_layers)))
+        mats = list(ex.map(draw, jobs))
+        top = list(ex.map(lambda i: normal_matrix(seed, _stream_id(3, i), (cfg.vocab, cfg.d_model), std, cfg.dtype),
+                          range(2)))
+    layers = []
+    for li in range(cfg.n_layers):
+        lw = {name: mats[li * len(_LAYER_MATS) + mi] for mi, name in enumerate(_LAYER_MATS)}
+        lw["norm_attn"] = gain(_stream_id(2, li, 0))
+        lw["norm_ffn"] = gain(_stream_id(2, li, 1))
+        layers.append(lw)
     w = {"layers": layers}
-    w["emb"] = normal_matrix(seed, _stream_id(3, 0), (cfg.vocab, cfg.d_model), std, cfg.dtype)
-    w["lm_head"] = normal_matrix(seed, _stream_id(3, 1), (cfg.vocab, cfg.d_model), std, cfg.dtype)
+    w["emb"], w["lm_head"] = top
     w["final_norm"] = gain(_stream_id(2, 1 << 20, 0))
     return w
 
