@@ -10,9 +10,13 @@ namespace ded {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
+// Weights: 64-feature group -> k step -> 4 feature tiles -> lane: the order a GEMM wavefront reads them,
+// so that every wavefront walks one contiguous stream.  Feature counts are padded to a multiple of 64.
+constexpr int PACKW_TILES = 4;
 __host__ __device__ inline int64_t packw_index(int n, int k, int K) {
   int lane = (((k & 31) >> 3) << 4) | (n & 15);
-  return ((((int64_t)(n >> 4) * (K >> 5) + (k >> 5)) << 6) + lane) * 8 + (k & 7);
+  int64_t frag = ((int64_t)(n >> 6) * (K >> 5) + (k >> 5)) * PACKW_TILES + ((n >> 4) & 3);
+  return ((frag << 6) + lane) * 8 + (k & 7);
 }
 __host__ __device__ inline int64_t packx_index(int r, int k, int RB) {
   int lane = (((k & 31) >> 3) << 4) | (r & 15);

@@ -172,8 +172,12 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
   const int L = c.n_layers;
   auto bytes = [&](int64_t n) { return (size_t)n * z.elem; };
 
+  // bf16 matrices are re-laid-out with the feature count padded to a multiple of 64
+  auto wbytes = [&](int64_t n_out, int64_t k_in) {
+    return bytes((c.dtype == DED_BF16 ? (n_out + 63) / 64 * 64 : n_out) * k_in);
+  };
   char* emb = w.take<char>(bytes(V * d));
-  char* lm = w.take<char>(bytes(V * d));
+  char* lm = w.take<char>(wbytes(V, d));
   float* fn = w.take<float>(d);
   if (ctx) {
     ctx->emb = emb;
@@ -187,10 +191,10 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
     ctx->norm_ffn.assign(L, nullptr);
   }
   for (int l = 0; l < L; ++l) {
-    char* a = w.take<char>(bytes(qkv_n * d));
-    char* b = w.take<char>(bytes(d * qd));
-    char* g = w.take<char>(bytes(2 * F * d));
-    char* dn = w.take<char>(bytes(d * F));
+    char* a = w.take<char>(wbytes(qkv_n, d));
+    char* b = w.take<char>(wbytes(d, qd));
+    char* g = w.take<char>(wbytes(2 * F, d));
+    char* dn = w.take<char>(wbytes(d, F));
     float* na = w.take<float>(d);
     float* nf = w.take<float>(d);
     if (ctx) {
@@ -463,11 +467,12 @@ int forward_bf16(ded_ctx* c) {
   hipStream_t s = c->stream;
   const int d = md.d, qd = md.H * md.hd, kvd = md.Hkv * md.hd, qkv_n = qd + 2 * kvd, F = md.F;
   const int rows_pad = round_up(m.rows, 64);
+  bool ok = true;
   auto gemm = [&](int cls, const bf16_t* xp, const void* w, int N, int K, int* splits_out) {
     int S = bf16_gemm_pick_splits(rows_pad, N, K);
     while (S > 1 && (int64_t)S * rows_pad * N > c->part_elems) --S;
     ProfScope p(c, cls);
-    bf16_gemm(c->part, (int64_t)rows_pad * N, xp, (const bf16_t*)w, rows_pad, N, K, S, N, s);
+    ok = bf16_gemm(c->part, (int64_t)rows_pad * N, xp, (const bf16_t*)w, rows_pad, N, K, S, N, s) && ok;
     *splits_out = S;
   };
   { ProfScope p(c, KC_ROPE_TABLE); launch_rope_table(c->rope_tab, m.pos, m.rows, md.hd, md.rope_base, s); }
@@ -496,7 +501,8 @@ int forward_bf16(ded_ctx* c) {
   { ProfScope p(c, KC_RMSNORM);
     bf16_add_rmsnorm(c->x, c->part, S_prev, (int64_t)rows_pad * d, c->y_p, c->final_norm, m.rows, rows_pad, d, md.eps, s); }
   { ProfScope p(c, KC_GEMM_LM_HEAD);
-    bf16_gemm(c->logits, 0, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 1, md.V, s); }
+    ok = bf16_gemm(c->logits, 0, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 1, md.V, s) && ok; }
+  if (!ok) return DED_EINVAL;
   return launch_status();
 }
 

@@ -62,7 +62,8 @@ void f32_gather_rows(float* dst, const float* src, const StepMeta& m, int max_no
 
 // ---- bf16 path ---------------------------------------------------------------------------
 // Operand-fragment layouts (units: bf16 elements; a fragment = 64 lanes x 8 elements = 1 KiB):
-//  PackW  W[N][K]   : frag (nt = n/16, kt = k/32) at nt*(K/32)+kt; lane = ((k%32)/8)*16 + n%16; elem k%8
+//  PackW  W[N][K]   : frag (ng = n/64, kt = k/32, t = (n/16)%4) at (ng*(K/32)+kt)*4+t; lane = ((k%32)/8)*16 + n%16;
+//                      elem k%8; N padded to a multiple of 64 with zero features
 //  PackX  X[R][K]   : frag (kt, rb = r/16) at kt*RB+rb;            lane = ((k%32)/8)*16 + r%16; elem k%8
 //  PackQ  per (b,kvh): frag (vrb, kk = hd/32) at vrb*4+kk, virtual row vr = g*n_step + node
 //  PackK  per (b,kvh): 32-key group kb; frag (kb, c, kk) at (kb*2+c)*4+kk; key%32 = q8*8 + c*4 + i
@@ -76,8 +77,8 @@ void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream
 void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
                       const float* gain, int rows, int rows_pad, int d, float eps, hipStream_t s);
 // Skinny GEMM on the matrix cores: part[s][r][n] = sum_{k in slice s} X[r][k] W[n][k], fp32.
-// rows_pad % 64 == 0, N % 16 == 0, K % 128 == 0, 1 <= splits <= K/128.
-void bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed,
+// rows_pad % 64 == 0, N % 16 == 0, K % 128 == 0, 1 <= splits <= K/128; returns false (nothing launched) otherwise.
+bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed,
                int rows_pad, int N, int K, int splits, int64_t out_row_stride, hipStream_t s);
 int bf16_gemm_pick_splits(int rows_pad, int N, int K);
 // sum partials, rotate q/k, write PackQ and the cache fragments

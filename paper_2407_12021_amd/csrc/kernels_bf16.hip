@@ -55,20 +55,23 @@ __device__ inline F8 sum_parts8(const float* part, int n_part, int64_t part_stri
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
+// dst: PackW with the feature count padded to a multiple of 64 (padding features are zero)
 __global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K) {
   int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // destination 16-byte unit
-  int64_t total = (int64_t)N * K / 8;
+  int64_t total = (int64_t)((N + 63) / 64 * 64) * K / 8;
   if (u >= total) return;
   int lane = (int)(u & 63);
   int64_t frag = u >> 6;
   int KT = K >> 5;
-  int nt = (int)(frag / KT), kt = (int)(frag - (int64_t)nt * KT);
-  int n = nt * 16 + (lane & 15);
+  int t = (int)(frag % PACKW_TILES);
+  int64_t gk = frag / PACKW_TILES;
+  int kt = (int)(gk % KT), ng = (int)(gk / KT);
+  int n = ng * 64 + t * 16 + (lane & 15);
   int k = kt * 32 + (lane >> 4) * 8;
-  dst[u] = *reinterpret_cast<const uint4*>(src + (int64_t)n * K + k);
+  dst[u] = n < N ? *reinterpret_cast<const uint4*>(src + (int64_t)n * K + k) : make_uint4(0, 0, 0, 0);
 }
 void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, hipStream_t s) {
-  int64_t units = (int64_t)N * K / 8;
+  int64_t units = (int64_t)((N + 63) / 64 * 64) * K / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
                      reinterpret_cast<uint4*>(dst), src, N, K);
 }
