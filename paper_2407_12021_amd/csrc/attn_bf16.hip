@@ -69,22 +69,34 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   for (int hb = 0; hb < 8; ++hb) o[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = NEG_BIG, l_run = 0.f;
 
-  uint4 stage[8];
+  // global -> register -> LDS staging of one tile (kept in eight named registers per thread)
+  struct Stage {
+    uint4 k0, k1, k2, k3, v0, v1, v2, v3;
+  };
   auto load_tile = [&](int t) {
     const uint4* ks = kbase + (int64_t)t * TILE_U4 + tid;
     const uint4* vs = vbase + (int64_t)t * TILE_U4 + tid;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      stage[i] = ks[i * 256];
-      stage[4 + i] = vs[i * 256];
-    }
+    Stage st;
+    st.k0 = ks[0];
+    st.k1 = ks[256];
+    st.k2 = ks[512];
+    st.k3 = ks[768];
+    st.v0 = vs[0];
+    st.v1 = vs[256];
+    st.v2 = vs[512];
+    st.v3 = vs[768];
+    return st;
   };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      lds[buf][i * 256 + tid] = stage[i];
-      lds[buf][TILE_U4 + i * 256 + tid] = stage[4 + i];
-    }
+  auto store_tile = [&](int buf, const Stage& st) {
+    uint4* d = lds[buf] + tid;
+    d[0] = st.k0;
+    d[256] = st.k1;
+    d[512] = st.k2;
+    d[768] = st.k3;
+    d[TILE_U4] = st.v0;
+    d[TILE_U4 + 256] = st.v1;
+    d[TILE_U4 + 512] = st.v2;
+    d[TILE_U4 + 768] = st.v3;
   };
 
   auto compute_tile = [&](int buf, int t) {
@@ -166,15 +178,15 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   };
 
   if (t_begin < t_end) {
-    load_tile(t_begin);
-    store_tile(0);
+    store_tile(0, load_tile(t_begin));
     __syncthreads();
     int buf = 0;
     for (int t = t_begin; t < t_end; ++t) {
-      const bool more = t + 1 < t_end;
-      if (more) load_tile(t + 1);
+      // the last iteration re-fetches its own tile (in bounds, L2 hit) so that the loop body is branch free
+      const int t_next = t + 1 < t_end ? t + 1 : t;
+      Stage st = load_tile(t_next);
       if (active) compute_tile(buf, t);
-      if (more) store_tile(buf ^ 1);
+      store_tile(buf ^ 1, st);
       __syncthreads();
       buf ^= 1;
     }
