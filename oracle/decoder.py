@@ -21,12 +21,27 @@ from __future__ import annotations
 import numpy as np
 
 
-def widen(a: np.ndarray) -> np.ndarray:
-    """Exact conversion to fp64.  uint16 arrays are bf16 bit patterns."""
-    a = np.asarray(a)
+def _widen_block(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     return a.astype(np.float64)
+
+
+def widen(a: np.ndarray) -> np.ndarray:
+    """Exact conversion to fp64.  uint16 arrays are bf16 bit patterns.  (Large matrices are converted
+    in row blocks on a few threads; the arithmetic is the same element-wise widening.)"""
+    a = np.asarray(a)
+    if a.ndim == 2 and a.size >= (1 << 24):
+        from concurrent.futures import ThreadPoolExecutor
+        out = np.empty(a.shape, dtype=np.float64)
+        step = max(1, (1 << 22) // a.shape[1])
+
+        def job(r0):
+            out[r0:r0 + step] = _widen_block(a[r0:r0 + step])
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(job, range(0, a.shape[0], step)))
+        return out
+    return _widen_block(a)
 
 
 def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:

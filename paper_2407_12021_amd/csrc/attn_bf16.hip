@@ -1,4 +1,4 @@
-// Tree-masked attention for the bf16 path (head_dim 128), split over the key axis.
+// Tree-masked attention for the 16-bit path (f16 K/V cache, head_dim 128), split over the key axis.
 //
 // Work unit: (sequence, kv head, tile of 64 "virtual rows", key range).  The virtual rows of a kv head
 // are its G query heads x n_step tree rows (vr = g * n_step + node), so grouped-query heads share
@@ -6,7 +6,7 @@
 // keys: the K and V^T fragments of a tile (32 KiB, contiguous in the cache) are fetched with fully
 // coalesced 16-byte loads, parked in LDS (double buffered) and consumed by all four wavefronts, each
 // of which owns 16 of the 64 rows:
-//     S^T = K . Q^T           v_mfma_f32_16x16x32_bf16, A = key fragment (LDS), B = query fragment (VGPR)
+//     S^T = K . Q^T           v_mfma_f32_16x16x32_f16, A = key fragment (LDS), B = query fragment (VGPR)
 //     online soft-max          per lane: 1 row, 16 keys of the tile; row max via two wavefront shuffles
 //     O^T += V^T . P^T         A = value fragment (LDS), B = probabilities straight from the S^T registers
 // The key rows of a 32-key group are interleaved inside the two 16-row tiles (see packk_index) so that
@@ -14,7 +14,7 @@
 // product needs, with no cross-lane traffic.  The ancestor mask is a per-row bitmask over tree slots;
 // tiles that lie entirely inside the prefix skip all mask work.
 // Each workgroup writes (running max, sum, unnormalised output) per row; a second kernel merges the
-// key ranges in a fixed order and writes bf16 output in PackX for the O projection.
+// key ranges in a fixed order and writes the output as hi/lo f16 in PackX for the O projection.
 #include <algorithm>
 
 #include "bf16_layout.h"
@@ -51,14 +51,14 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   const int node = active ? vr - g * n_step : 0;
   const uint64_t* mrow = mask + ((int64_t)b * n_step + node) * 4;
 
-  bf16x8_t q[4];
+  f16x8_t q[8];  // [head-dim chunk kk][plane hi / lo]
   if (active) {
-    const uint4* qsrc = qp + (((int64_t)bz * (VR / 16) + vrb) * 4 << 6) + lane;
+    const uint4* qsrc = qp + (((int64_t)bz * (VR / 16) + vrb) * 8 << 6) + lane;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) q[kk] = __builtin_bit_cast(bf16x8_t, qsrc[kk << 6]);
+    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, qsrc[i << 6]);
   } else {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) q[kk] = __builtin_bit_cast(bf16x8_t, make_uint4(0, 0, 0, 0));
+    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, make_uint4(0, 0, 0, 0));
   }
 
   const uint4* kbase = kc + (int64_t)bz * cap * 16;  // 16 uint4 per key
@@ -109,12 +109,14 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        f32x4_t acc_lo = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          bf16x8_t a = __builtin_bit_cast(bf16x8_t, lk[(((kb * 2 + c) * 4 + kk) << 6) + lane]);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, q[kk], acc, 0, 0, 0);
+          f16x8_t a = __builtin_bit_cast(f16x8_t, lk[(((kb * 2 + c) * 4 + kk) << 6) + lane]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, q[2 * kk], acc, 0, 0, 0);
+          acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, q[2 * kk + 1], acc_lo, 0, 0, 0);
         }
-        s[kb][c] = acc;
+        s[kb][c] = acc + acc_lo;
       }
     const int key0 = t * TILE;
     float p[2][8];
@@ -148,19 +150,16 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     const float m_new = fmaxf(m_run, mx);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     float lsum = 0.f;
-    bf16x8_t pb[2];
+    f16x8_t pb[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      uint32_t w[4];
 #pragma unroll
-      for (int j = 0; j < 8; j += 2) {
-        float e0 = p[kb][j] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[kb][j] - m_new) : 0.f;
-        float e1 = p[kb][j + 1] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[kb][j + 1] - m_new) : 0.f;
-        uint16_t h0 = f32_to_bf16(e0), h1 = f32_to_bf16(e1);
-        lsum += bf16_to_f32(h0) + bf16_to_f32(h1);  // the sum uses the rounded weights the product uses
-        w[j >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      for (int j = 0; j < 8; ++j) {
+        float e = p[kb][j] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[kb][j] - m_new) : 0.f;
+        _Float16 h = (_Float16)e;
+        lsum += (float)h;  // the sum uses the rounded weights the product uses
+        pb[kb][j] = h;
       }
-      pb[kb] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
     }
     l_run = l_run * alpha + lsum;
     m_run = m_new;
@@ -172,8 +171,8 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int hb = 0; hb < 8; ++hb) {
-        bf16x8_t a = __builtin_bit_cast(bf16x8_t, lv[((kb * 8 + hb) << 6) + lane]);
-        o[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[kb], o[hb], 0, 0, 0);
+        f16x8_t a = __builtin_bit_cast(f16x8_t, lv[((kb * 8 + hb) << 6) + lane]);
+        o[hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[kb], o[hb], 0, 0, 0);
       }
   };
 
@@ -223,7 +222,10 @@ __global__ __launch_bounds__(128) void tree_attn_merge_kernel(bf16_t* __restrict
     L += ml.y * w;
     acc += part_o[(base + (int64_t)s * n_step) * 128 + i] * w;
   }
-  op[packx_index(r, h * 128 + i, RB)] = f32_to_bf16(acc / L);
+  uint16_t hi, lo;
+  split_f16(acc / L, hi, lo);
+  op[packx_index(r, h * 128 + i, RB, 0)] = hi;
+  op[packx_index(r, h * 128 + i, RB, 1)] = lo;
 }
 
 }  // namespace

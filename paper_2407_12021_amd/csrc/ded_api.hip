@@ -232,10 +232,11 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
       ctx->f_h = h;
     }
   } else {
-    bf16_t* y = w.take<bf16_t>((int64_t)z.max_rows_pad * d);
-    bf16_t* o = w.take<bf16_t>((int64_t)z.max_rows_pad * qd);
-    bf16_t* h = w.take<bf16_t>((int64_t)z.max_rows_pad * std::max<int64_t>(F, 1));
-    bf16_t* q = w.take<bf16_t>((int64_t)z.max_rows_pad * qd);
+    // GEMM inputs and queries are kept as hi/lo pairs of f16: two planes each
+    bf16_t* y = w.take<bf16_t>((int64_t)z.max_rows_pad * d * 2);
+    bf16_t* o = w.take<bf16_t>((int64_t)z.max_rows_pad * qd * 2);
+    bf16_t* h = w.take<bf16_t>((int64_t)z.max_rows_pad * std::max<int64_t>(F, 1) * 2);
+    bf16_t* q = w.take<bf16_t>((int64_t)z.max_rows_pad * qd * 2);
     // split-K partials: at most 8 slices of 64 rows, or one slice of every row
     int64_t widest = std::max<int64_t>(std::max<int64_t>(qkv_n, 2 * F), d);
     int64_t part_elems = widest * std::max<int64_t>(8 * 64, z.max_rows_pad);

@@ -38,6 +38,15 @@ constexpr int RING = DED_GEMM_RING;  // k steps in flight per wavefront (1, 2 or
 #define DED_GEMM_MINW 2
 #endif
 
+#ifdef DED_GEMM_TRACE
+__device__ unsigned long long* g_trace = nullptr;  // [wave][4] wall-clock stamps (debug builds only)
+#define DED_STAMP(i)                                                                              \
+  if (g_trace && lane == 0)                                                                       \
+    g_trace[(((size_t)(blockIdx.y * gridDim.x + blockIdx.x)) * NW + wave) * 4 + (i)] = wall_clock64();
+#else
+#define DED_STAMP(i)
+#endif
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64, DED_GEMM_MINW) void gemm_stream_kernel(
     float* __restrict__ part, int64_t part_stride, const uint4* __restrict__ xp, const uint4* __restrict__ wp,
@@ -59,30 +68,34 @@ __global__ __launch_bounds__(NW * 64, DED_GEMM_MINW) void gemm_stream_kernel(
   for (int t = 0; t < TN; ++t)
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  DED_STAMP(0)
 
   if (g_begin < g_end) {
     const uint4* wsrc = wp + (((int64_t)ng * KT * TN) << 6) + lane;
-    const uint4* xsrc = xp + ((int64_t)rb0 << 6) + lane;
-    const int64_t xstep = (int64_t)RB << 6;
+    // per k step the activations of the 4 row blocks x 2 planes (hi, lo) are 8 KiB of contiguous memory
+    const uint4* xsrc = xp + ((int64_t)rb0 << 7) + lane;
+    const int64_t xstep = (int64_t)RB << 7;
 
-    uint4 wr[RING][TN], xr[RING][4];
+    uint4 wr[RING][TN], xr[RING][8];
     auto issue = [&](int slot, int kt) {
 #pragma unroll
       for (int t = 0; t < TN; ++t) wr[slot][t] = wsrc[((int64_t)kt * TN + t) << 6];
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) xr[slot][rb] = xsrc[kt * xstep + (rb << 6)];
+      for (int i = 0; i < 8; ++i) xr[slot][i] = xsrc[kt * xstep + (i << 6)];
     };
     auto compute = [&](int slot) {
-      bf16x8_t b[4];
+      f16x8_t b[8];
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) b[rb] = __builtin_bit_cast(bf16x8_t, xr[slot][rb]);
+      for (int i = 0; i < 8; ++i) b[i] = __builtin_bit_cast(f16x8_t, xr[slot][i]);
 #pragma unroll
-      for (int t = 0; t < TN; ++t) {
-        bf16x8_t a = __builtin_bit_cast(bf16x8_t, wr[slot][t]);
+      for (int plane = 0; plane < 2; ++plane)  // 16 independent accumulators between dependent products
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
-          acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[rb], acc[t][rb], 0, 0, 0);
-      }
+        for (int t = 0; t < TN; ++t) {
+          f16x8_t a = __builtin_bit_cast(f16x8_t, wr[slot][t]);
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
+            acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[2 * rb + plane], acc[t][rb], 0, 0, 0);
+        }
     };
 
     int kt = g_begin * PD;
@@ -99,6 +112,7 @@ __global__ __launch_bounds__(NW * 64, DED_GEMM_MINW) void gemm_stream_kernel(
 #pragma unroll
     for (int j = 0; j < RING; ++j) compute(j);
   }
+  DED_STAMP(1)
 
   // combine the NW k ranges: wave w += wave w + stride, stride = NW/2 .. 1
   if (NW > 1) {
@@ -129,6 +143,7 @@ __global__ __launch_bounds__(NW * 64, DED_GEMM_MINW) void gemm_stream_kernel(
     }
   }
 
+  DED_STAMP(2)
   if (wave == 0) {
     float* out = part + (int64_t)split * part_stride;
     const int row_in = lane & 15, quad = lane >> 4;
@@ -144,6 +159,7 @@ __global__ __launch_bounds__(NW * 64, DED_GEMM_MINW) void gemm_stream_kernel(
       }
     }
   }
+  DED_STAMP(3)
 }
 
 struct GemmPlan {

@@ -1,6 +1,6 @@
-// bf16 path, everything that is not a contraction: weight re-layout, embedding gather, residual add +
+// 16-bit path, everything that is not a contraction: weight re-layout, embedding gather, residual add +
 // RMSNorm, the QKV epilogue (split-K sum, rotary embedding, cache append), SiLU*up, cache compaction
-// and the plain <-> fragment layout conversions.
+// and the plain <-> fragment layout conversions.  Number formats: see bf16_layout.h.
 #include <algorithm>
 
 #include "bf16_layout.h"
@@ -37,9 +37,19 @@ __device__ inline void store8(float* p, const F8& r) {
   *reinterpret_cast<float4*>(p) = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
   *reinterpret_cast<float4*>(p + 4) = make_float4(r.v[4], r.v[5], r.v[6], r.v[7]);
 }
-__device__ inline uint4 to_bf16x8(const F8& r) {
-  return make_uint4(pack2_bf16(r.v[0], r.v[1]), pack2_bf16(r.v[2], r.v[3]), pack2_bf16(r.v[4], r.v[5]),
-                    pack2_bf16(r.v[6], r.v[7]));
+__device__ inline uint32_t pk(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
+// eight floats -> eight f16 (one 16-byte unit)
+__device__ inline uint4 to_f16x8(const F8& r) {
+  return make_uint4(pk(f32_to_f16(r.v[0]), f32_to_f16(r.v[1])), pk(f32_to_f16(r.v[2]), f32_to_f16(r.v[3])),
+                    pk(f32_to_f16(r.v[4]), f32_to_f16(r.v[5])), pk(f32_to_f16(r.v[6]), f32_to_f16(r.v[7])));
+}
+// eight floats -> hi and lo planes
+__device__ inline void to_f16x8_split(const F8& r, uint4& hi, uint4& lo) {
+  uint16_t h[8], l[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) split_f16(r.v[i], h[i], l[i]);
+  hi = make_uint4(pk(h[0], h[1]), pk(h[2], h[3]), pk(h[4], h[5]), pk(h[6], h[7]));
+  lo = make_uint4(pk(l[0], l[1]), pk(l[2], l[3]), pk(l[4], l[5]), pk(l[6], l[7]));
 }
 // sum over split-K slices in slice order (fixed order -> deterministic)
 __device__ inline F8 sum_parts8(const float* part, int n_part, int64_t part_stride, int64_t off) {
@@ -55,7 +65,7 @@ __device__ inline F8 sum_parts8(const float* part, int n_part, int64_t part_stri
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
-// dst: PackW with the feature count padded to a multiple of 64 (padding features are zero)
+// dst: PackW (f16) with the feature count padded to a multiple of 64 (padding features are zero)
 __global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K) {
   int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // destination 16-byte unit
   int64_t total = (int64_t)((N + 63) / 64 * 64) * K / 8;
@@ -68,7 +78,15 @@ __global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __rest
   int kt = (int)(gk % KT), ng = (int)(gk / KT);
   int n = ng * 64 + t * 16 + (lane & 15);
   int k = kt * 32 + (lane >> 4) * 8;
-  dst[u] = n < N ? *reinterpret_cast<const uint4*>(src + (int64_t)n * K + k) : make_uint4(0, 0, 0, 0);
+  uint4 out = make_uint4(0, 0, 0, 0);
+  if (n < N) {
+    uint4 in = *reinterpret_cast<const uint4*>(src + (int64_t)n * K + k);
+    uint32_t w[4] = {in.x, in.y, in.z, in.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pk(bf16_to_f16((uint16_t)(w[i] & 0xffffu)), bf16_to_f16((uint16_t)(w[i] >> 16)));
+    out = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  dst[u] = out;
 }
 void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, hipStream_t s) {
   int64_t units = (int64_t)((N + 63) / 64 * 64) * K / 8;
@@ -88,7 +106,7 @@ void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream
 }
 
 // ------------------------------------------------------------------------------------------
-// x[r] += sum of the pending split-K slices; y = bf16(x * rsqrt(mean(x^2) + eps) * gain) in PackX.
+// x[r] += sum of the pending split-K slices; y = x * rsqrt(mean(x^2) + eps) * gain as hi/lo f16 in PackX.
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part,
                                                           int n_part, int64_t part_stride, uint4* __restrict__ y,
                                                           const float* __restrict__ gain, int RB, int d, float eps) {
@@ -114,7 +132,10 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ x,
     F8 g = load8(gain + u * 8);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v.v[i] = v.v[i] * inv * g.v[i];
-    y[packx_index(r, u * 8, RB) >> 3] = to_bf16x8(v);
+    uint4 hi, lo;
+    to_f16x8_split(v, hi, lo);
+    y[packx_index(r, u * 8, RB, 0) >> 3] = hi;
+    y[packx_index(r, u * 8, RB, 1) >> 3] = lo;
   }
 }
 void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
@@ -126,8 +147,8 @@ void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stri
 
 // ------------------------------------------------------------------------------------------
 // QKV epilogue.  One thread owns 8 head dims i0..i0+7 of the first half of a head and their rotary
-// partners i0+64..i0+71.  Query heads go to PackQ, key heads (rotated) and value heads of real nodes
-// go to the cache fragments at slot prefix_len + node.
+// partners i0+64..i0+71.  Query heads go to PackQ (hi/lo), key heads (rotated) and value heads of real
+// nodes go to the cache fragments (f16) at slot prefix_len + node.
 __global__ __launch_bounds__(256) void qkv_epilogue_kernel(
     const float* __restrict__ part, int n_part, int64_t part_stride, bf16_t* __restrict__ qp,
     bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, const float2* __restrict__ tab,
@@ -156,23 +177,27 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(
         c.v[i] = rc;
       }
     }
-    uint4 lo = to_bf16x8(a), hi = to_bf16x8(c);
     if (hs < H) {
       int kvh = hs / G, g = hs - kvh * G;
       int vr = g * n_step + node;
-      bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd);
-      *reinterpret_cast<uint4*>(base + packq_index(vr, i0)) = lo;
-      *reinterpret_cast<uint4*>(base + packq_index(vr, i0 + half)) = hi;
+      bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd * 2);
+      uint4 hi, lo;
+      to_f16x8_split(a, hi, lo);
+      *reinterpret_cast<uint4*>(base + packq_index(vr, i0, 0)) = hi;
+      *reinterpret_cast<uint4*>(base + packq_index(vr, i0, 1)) = lo;
+      to_f16x8_split(c, hi, lo);
+      *reinterpret_cast<uint4*>(base + packq_index(vr, i0 + half, 0)) = hi;
+      *reinterpret_cast<uint4*>(base + packq_index(vr, i0 + half, 1)) = lo;
     } else if (hs < H + Hkv) {
       bf16_t* base = kc + ((int64_t)b * Hkv + (hs - H)) * ((int64_t)cap * hd);
-      *reinterpret_cast<uint4*>(base + packk_index(slot, i0)) = lo;
-      *reinterpret_cast<uint4*>(base + packk_index(slot, i0 + half)) = hi;
+      *reinterpret_cast<uint4*>(base + packk_index(slot, i0)) = to_f16x8(a);
+      *reinterpret_cast<uint4*>(base + packk_index(slot, i0 + half)) = to_f16x8(c);
     } else {
       bf16_t* base = vc + ((int64_t)b * Hkv + (hs - H - Hkv)) * ((int64_t)cap * hd);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        base[packvt_index(slot, i0 + i)] = f32_to_bf16(a.v[i]);
-        base[packvt_index(slot, i0 + half + i)] = f32_to_bf16(c.v[i]);
+        base[packvt_index(slot, i0 + i)] = f32_to_f16(a.v[i]);
+        base[packvt_index(slot, i0 + half + i)] = f32_to_f16(c.v[i]);
       }
     }
   }
@@ -196,7 +221,10 @@ __global__ void silu_mul_kernel(uint4* __restrict__ h, const float* __restrict__
   F8 up = sum_parts8(part, n_part, part_stride, off + F);
 #pragma unroll
   for (int i = 0; i < 8; ++i) g.v[i] = g.v[i] / (1.0f + __expf(-g.v[i])) * up.v[i];
-  h[packx_index(r, u * 8, RB) >> 3] = to_bf16x8(g);
+  uint4 hi, lo;
+  to_f16x8_split(g, hi, lo);
+  h[packx_index(r, u * 8, RB, 0) >> 3] = hi;
+  h[packx_index(r, u * 8, RB, 1) >> 3] = lo;
 }
 void bf16_silu_mul(bf16_t* h_packed, const float* part, int n_part, int64_t part_stride, int rows, int rows_pad,
                    int F, hipStream_t s) {
@@ -244,6 +272,7 @@ void bf16_kv_compact(bf16_t* const* kc, bf16_t* const* vc, const int32_t* path, 
 }
 
 // ------------------------------------------------------------------------------------------
+// plain bf16 [Hkv][n][hd]  <->  f16 cache fragments (to the cache: exact widening; back: round to bf16)
 __global__ void bf16_kv_copy_kernel(bf16_t* __restrict__ kcache, bf16_t* __restrict__ vcache,
                                     bf16_t* __restrict__ kp, bf16_t* __restrict__ vp, int to_cache, int seq,
                                     int first, int n, int Hkv, int cap) {
@@ -253,11 +282,11 @@ __global__ void bf16_kv_copy_kernel(bf16_t* __restrict__ kcache, bf16_t* __restr
   int64_t pidx = ((int64_t)g * n + j) * hd + i;
   int64_t ki = cbase + packk_index(first + j, i), vi = cbase + packvt_index(first + j, i);
   if (to_cache) {
-    if (kp) kcache[ki] = kp[pidx];
-    if (vp) vcache[vi] = vp[pidx];
+    if (kp) kcache[ki] = bf16_to_f16(kp[pidx]);
+    if (vp) vcache[vi] = bf16_to_f16(vp[pidx]);
   } else {
-    if (kp) kp[pidx] = kcache[ki];
-    if (vp) vp[pidx] = vcache[vi];
+    if (kp) kp[pidx] = f32_to_bf16(f16_to_f32(kcache[ki]));
+    if (vp) vp[pidx] = f32_to_bf16(f16_to_f32(vcache[vi]));
   }
 }
 void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_plain, bool to_cache, int seq,
@@ -278,8 +307,8 @@ __global__ void bf16_scatter_tree_kv_kernel(bf16_t* __restrict__ kc, bf16_t* __r
   int64_t src = ((int64_t)bh * max_nodes + node) * hd + i;
   int64_t cbase = (int64_t)bh * cap * hd;
   int slot = seq_p[b] + node;
-  kc[cbase + packk_index(slot, i)] = kt[src];
-  vc[cbase + packvt_index(slot, i)] = vt[src];
+  kc[cbase + packk_index(slot, i)] = bf16_to_f16(kt[src]);
+  vc[cbase + packvt_index(slot, i)] = bf16_to_f16(vt[src]);
 }
 void bf16_scatter_tree_kv(bf16_t* kc, bf16_t* vc, const bf16_t* k_tree, const bf16_t* v_tree, const StepMeta& m,
                           const ModelDims& md, int max_nodes, hipStream_t s) {
@@ -287,17 +316,18 @@ void bf16_scatter_tree_kv(bf16_t* kc, bf16_t* vc, const bf16_t* k_tree, const bf
                      k_tree, v_tree, m.seq_p, m.seq_n, md.Hkv, md.cap, max_nodes);
 }
 
-// q plain [B][max_nodes][H][hd] -> PackQ (rows of absent nodes become zero)
+// q plain bf16 [B][max_nodes][H][hd] -> PackQ (hi = exact f16, lo = 0; rows of absent nodes become zero)
 __global__ void bf16_pack_q_kernel(bf16_t* __restrict__ qp, const bf16_t* __restrict__ q,
                                    const int32_t* __restrict__ seq_n, int n_step, int H, int Hkv, int max_nodes) {
   const int hd = 128;
   int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
   int b = r / n_step, node = r - b * n_step;
   int G = H / Hkv, kvh = h / G, g = h - kvh * G;
-  bf16_t v = 0;
-  if (node < seq_n[b]) v = q[(((int64_t)b * max_nodes + node) * H + h) * hd + i];
-  bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd);
-  base[packq_index(g * n_step + node, i)] = v;
+  uint16_t hi = 0, lo = 0;
+  if (node < seq_n[b]) split_f16(bf16_to_f32(q[(((int64_t)b * max_nodes + node) * H + h) * hd + i]), hi, lo);
+  bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd * 2);
+  base[packq_index(g * n_step + node, i, 0)] = hi;
+  base[packq_index(g * n_step + node, i, 1)] = lo;
 }
 void bf16_pack_q(bf16_t* q_packed, const bf16_t* q_plain, const StepMeta& m, const ModelDims& md, int max_nodes,
                  hipStream_t s) {
@@ -305,14 +335,15 @@ void bf16_pack_q(bf16_t* q_packed, const bf16_t* q_plain, const StepMeta& m, con
                      md.H, md.Hkv, max_nodes);
 }
 
-// PackX(o) [rows_pad][H*hd] -> plain [B][max_nodes][H][hd]
+// PackX(o) hi + lo [rows_pad][H*hd] -> plain bf16 [B][max_nodes][H][hd]
 __global__ void bf16_unpack_o_kernel(bf16_t* __restrict__ out, const bf16_t* __restrict__ op,
                                      const int32_t* __restrict__ seq_n, int n_step, int H, int RB, int max_nodes) {
   const int hd = 128;
   int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
   int b = r / n_step, node = r - b * n_step;
   if (node >= seq_n[b]) return;
-  out[(((int64_t)b * max_nodes + node) * H + h) * hd + i] = op[packx_index(r, h * hd + i, RB)];
+  float v = f16_to_f32(op[packx_index(r, h * hd + i, RB, 0)]) + f16_to_f32(op[packx_index(r, h * hd + i, RB, 1)]);
+  out[(((int64_t)b * max_nodes + node) * H + h) * hd + i] = f32_to_bf16(v);
 }
 void bf16_unpack_o(bf16_t* out_plain, const bf16_t* o_packed, int rows_pad, const StepMeta& m, const ModelDims& md,
                    int max_nodes, hipStream_t s) {

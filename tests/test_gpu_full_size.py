@@ -1,0 +1,115 @@
+"""GPU parity at the benchmark configurations' full sizes (same launch configurations as bench.py)."""
+import time
+
+import numpy as np
+import pytest
+
+import ded_inputs as di
+import oracle
+
+pytestmark = pytest.mark.gpu
+MARGIN = 0.05
+
+
+def _verifier(*a, **k):
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2407_12021_amd import Verifier
+    return Verifier(*a, **k)
+
+
+def test_c2_attention_only_full_size():
+    """Config 2: one tree-attention layer, 32 heads x 128, 4096-key prefix ~ N(0,1), 64-node random tree of
+    depth 8, bf16.  Every output element is compared with the fp64 oracle."""
+    import torch
+    from paper_2407_12021_amd.binding import _to_device
+    wl = di.WORKLOADS["c2"]
+    H, hd, P, N = 32, 128, wl.prefix_len, wl.n_nodes
+    cfg = di.ModelConfig("attn-only", 1, 128, H, H, hd, 128, 16)
+    ver = _verifier(cfg, di.make_weights(cfg, seed=0), max_batch=1, kv_capacity=P + N, max_nodes=N)
+    x = di.attention_inputs(H, H, hd, P, N, seed=100)
+    parent = di.random_tree(N, wl.depth, seed=0)
+    assert di.tree_depths(parent).max() == 8
+    ver.kv_store(0, 0, 0, x["k_prefix"], x["v_prefix"])
+    q = _to_device(x["q"], ver.device, "bf16")[None]
+    kt = _to_device(x["k_tree"], ver.device, "bf16")[None]
+    vt = _to_device(x["v_tree"], ver.device, "bf16")[None]
+    out = ver.tree_attention(0, [P], [parent], q, kt, vt)
+    torch.cuda.synchronize()
+    got = out[0].float().cpu().numpy()
+    kk = np.concatenate([oracle.widen(x["k_prefix"]), oracle.widen(x["k_tree"])], axis=1).transpose(1, 0, 2)
+    vv = np.concatenate([oracle.widen(x["v_prefix"]), oracle.widen(x["v_tree"])], axis=1).transpose(1, 0, 2)
+    vis = np.concatenate([np.ones((N, P), bool), oracle.ancestor_mask(parent)], axis=1)
+    ref = oracle.masked_attention(oracle.widen(x["q"]), kk, vv, vis)
+    err = np.abs(got - ref).max()
+    print(f"c2: max |o error| {err:.3e} (|o| max {np.abs(ref).max():.2f})")
+    # o is stored in bf16: half an ulp at |o| < 1 is 2^-9; probabilities are rounded to bf16 before P.V
+    assert err <= 8e-3, err
+    # determinism: a second launch gives the same bits
+    out2 = ver.tree_attention(0, [P], [parent], q, kt, vt)
+    assert torch.equal(out, out2)
+    ver.close()
+
+
+def _full_step_check(cfg, wl, label):
+    t0 = time.time()
+    w = di.make_weights(cfg, seed=0, threads=16)
+    prefix, parent, token = di.workload_tree(wl, seed=0)
+    P, N = len(prefix), len(parent)
+    ver = _verifier(cfg, w, max_batch=1, kv_capacity=P + N + wl.depth + 2, max_nodes=N)
+    for s in range(0, P, N):
+        n = min(N, P - s)
+        ver.verify_step([s], [di.chain_tree(n)], [prefix[s:s + n]])
+        ver.accept(mode=1)
+    logits = ver.verify_step([P], [parent], [token], want_logits=True)[0, :N].cpu().numpy().astype(np.float64)
+    a_gpu, m_gpu = ver.get_argmax()
+    acc, path, newp = ver.accept(mode=0)
+    t_gpu = time.time() - t0
+    # oracle: one causal pass over prefix + tree rows (the tree rows see the prefix and their ancestors)
+    t0 = time.time()
+    vis = np.zeros((P + N, P + N), dtype=bool)
+    vis[:P, :P] = np.tril(np.ones((P, P), dtype=bool))
+    vis[P:, :P] = True
+    vis[P:, P:] = oracle.ancestor_mask(parent)
+    pos = np.concatenate([np.arange(P), P + oracle.node_depths(parent)])
+    ref_all, k_all, v_all = oracle.forward_rows(cfg, w, np.concatenate([prefix, token]), pos, vis)
+    ref = ref_all[P:]
+    t_cpu = time.time() - t0
+    err = np.abs(logits - ref).max()
+    a_ref, margin = oracle.argmax_margin(ref)
+    sure = margin > MARGIN
+    print(f"{label}: max |logit error| {err:.3e}; nodes under the {MARGIN} margin {int((~sure).sum())}/{N}; "
+          f"gpu side {t_gpu:.0f} s, oracle {t_cpu:.0f} s")
+    assert err <= 2e-2, err
+    assert (a_gpu[0, :N][sure] == a_ref[sure]).all()
+    acc2, path2 = oracle.accept_walk(parent, token, a_gpu[0, :N])
+    assert acc[0] == acc2 and path[0] == path2 and newp[0] == P + len(path2)
+    acc_ref, path_ref = oracle.accept_walk(parent, token, a_ref)
+    if all(sure[v] for v in set(path_ref) | set(path[0])):
+        assert acc[0] == acc_ref and path[0] == path_ref
+    # cache contents of the last layer after compaction (sampled: every 97th prefix slot + the kept path)
+    L = cfg.n_layers
+    k_gpu, v_gpu = ver.kv_load(L - 1, 0, 0, newp[0])
+    k_gpu = k_gpu.float().cpu().numpy().transpose(1, 0, 2)
+    v_gpu = v_gpu.float().cpu().numpy().transpose(1, 0, 2)
+    rows = list(range(0, P, 97)) + [P + v for v in path[0]]
+    slots = list(range(0, P, 97)) + [P + j for j in range(len(path[0]))]
+    kerr = np.abs(k_gpu[slots] - k_all[L - 1][rows]).max()
+    verr = np.abs(v_gpu[slots] - v_all[L - 1][rows]).max()
+    scale = max(1.0, np.abs(k_all[L - 1]).max())
+    print(f"{label}: last-layer cache error K {kerr:.3e} V {verr:.3e} (|K| max {scale:.2f})")
+    assert kerr <= 2e-2 * scale and verr <= 2e-2 * scale
+    ver.close()
+
+
+def test_c3_shape_two_layers():
+    """Config 3's shape (d 4096, 32 heads, ffn 11008, vocab 32000, prefix 1024, 64-node tree) with 2 layers."""
+    wl = di.WORKLOADS["c3"]
+    _full_step_check(wl.model.with_layers(2), wl, "c3-L2")
+
+
+def test_c3_full_model():
+    """Config 3 as benchmarked: all 32 layers, prefix K/V computed by chunked prefill on the GPU and by
+    a plain causal forward in the oracle."""
+    wl = di.WORKLOADS["c3"]
+    _full_step_check(wl.model, wl, "c3")
