@@ -469,12 +469,13 @@ int forward_bf16(ded_ctx* c) {
   const int d = md.d, qd = md.H * md.hd, kvd = md.Hkv * md.hd, qkv_n = qd + 2 * kvd, F = md.F;
   const int rows_pad = round_up(m.rows, 64);
   bool ok = true;
-  auto gemm = [&](int cls, const bf16_t* xp, const void* w, int N, int K, int* splits_out) {
-    int S = bf16_gemm_pick_splits(rows_pad, N, K);
-    while (S > 1 && (int64_t)S * rows_pad * N > c->part_elems) --S;
+  // planes: 2 = the input is consumed as hi + lo, 1 = hi only (enough for the O and down projections)
+  auto gemm = [&](int cls, const bf16_t* xp, const void* w, int N, int K, int planes, int* splits_out) {
+    GemmPlan plan = bf16_gemm_plan(rows_pad, N, K, planes);
+    while (plan.splits > 1 && (int64_t)plan.splits * rows_pad * N > c->part_elems) --plan.splits;
     ProfScope p(c, cls);
-    ok = bf16_gemm(c->part, (int64_t)rows_pad * N, xp, (const bf16_t*)w, rows_pad, N, K, S, N, s) && ok;
-    *splits_out = S;
+    ok = bf16_gemm(c->part, (int64_t)rows_pad * N, xp, (const bf16_t*)w, rows_pad, N, K, planes, plan, N, s) && ok;
+    *splits_out = plan.splits;
   };
   { ProfScope p(c, KC_ROPE_TABLE); launch_rope_table(c->rope_tab, m.pos, m.rows, md.hd, md.rope_base, s); }
   { ProfScope p(c, KC_EMBED); bf16_embed(c->x, (const bf16_t*)c->emb, m, d, s); }
@@ -483,7 +484,7 @@ int forward_bf16(ded_ctx* c) {
     { ProfScope p(c, KC_RMSNORM);
       bf16_add_rmsnorm(c->x, c->part, S_prev, (int64_t)rows_pad * d, c->y_p, c->norm_attn[l], m.rows, rows_pad, d, md.eps, s); }
     int S = 1;
-    gemm(KC_GEMM_QKV, c->y_p, c->wqkv[l], qkv_n, d, &S);
+    gemm(KC_GEMM_QKV, c->y_p, c->wqkv[l], qkv_n, d, 2, &S);
     { ProfScope p(c, KC_QKV_EPILOGUE);
       bf16_qkv_epilogue(c->part, S, (int64_t)rows_pad * qkv_n, c->q_p, (bf16_t*)c->kc[l], (bf16_t*)c->vc[l], c->rope_tab, m, md, s); }
     int ns = bf16_attn_pick_splits(m, md, c->max_p, c->attn_part_rows);
@@ -491,18 +492,21 @@ int forward_bf16(ded_ctx* c) {
       bf16_tree_attention_partial(c->q_p, (const bf16_t*)c->kc[l], (const bf16_t*)c->vc[l], c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
     { ProfScope p(c, KC_ATTN_MERGE);
       bf16_tree_attention_merge(c->o_p, rows_pad, c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
-    gemm(KC_GEMM_O, c->o_p, c->wo[l], d, qd, &S);
+    gemm(KC_GEMM_O, c->o_p, c->wo[l], d, qd, 1, &S);
     { ProfScope p(c, KC_RMSNORM);
       bf16_add_rmsnorm(c->x, c->part, S, (int64_t)rows_pad * d, c->y_p, c->norm_ffn[l], m.rows, rows_pad, d, md.eps, s); }
-    gemm(KC_GEMM_GATE_UP, c->y_p, c->wgu[l], 2 * F, d, &S);
+    gemm(KC_GEMM_GATE_UP, c->y_p, c->wgu[l], 2 * F, d, 2, &S);
     { ProfScope p(c, KC_SILU_MUL);
       bf16_silu_mul(c->h_p, c->part, S, (int64_t)rows_pad * 2 * F, m.rows, rows_pad, F, s); }
-    gemm(KC_GEMM_DOWN, c->h_p, c->wdown[l], d, F, &S_prev);
+    gemm(KC_GEMM_DOWN, c->h_p, c->wdown[l], d, F, 1, &S_prev);
   }
   { ProfScope p(c, KC_RMSNORM);
     bf16_add_rmsnorm(c->x, c->part, S_prev, (int64_t)rows_pad * d, c->y_p, c->final_norm, m.rows, rows_pad, d, md.eps, s); }
   { ProfScope p(c, KC_GEMM_LM_HEAD);
-    ok = bf16_gemm(c->logits, 0, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 1, md.V, s) && ok; }
+    GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, 2);
+    plan.splits = 1;  // the logits are written in place
+    plan.nw = 4;
+    ok = bf16_gemm(c->logits, 0, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 2, plan, md.V, s) && ok; }
   if (!ok) return DED_EINVAL;
   return launch_status();
 }

@@ -60,12 +60,12 @@ void f32_scatter_tree_kv(float* kc, float* vc, const float* k_tree, const float*
 void f32_gather_rows(float* dst, const float* src, const StepMeta& m, int max_nodes, int width,
                      bool to_padded, hipStream_t s);
 
-// ---- bf16 path ---------------------------------------------------------------------------
-// Operand-fragment layouts (units: bf16 elements; a fragment = 64 lanes x 8 elements = 1 KiB):
+// ---- 16-bit path (bf16 weights in, f16 matrix-core operands; see bf16_layout.h) -----------------
+// Operand-fragment layouts (units: 2-byte elements; a fragment = 64 lanes x 8 elements = 1 KiB):
 //  PackW  W[N][K]   : frag (ng = n/64, kt = k/32, t = (n/16)%4) at (ng*(K/32)+kt)*4+t; lane = ((k%32)/8)*16 + n%16;
 //                      elem k%8; N padded to a multiple of 64 with zero features
-//  PackX  X[R][K]   : frag (kt, rb = r/16) at kt*RB+rb;            lane = ((k%32)/8)*16 + r%16; elem k%8
-//  PackQ  per (b,kvh): frag (vrb, kk = hd/32) at vrb*4+kk, virtual row vr = g*n_step + node
+//  PackX  X[R][K]   : frag (kt, rb = r/16, plane hi/lo) at (kt*RB+rb)*2+plane; lane = ((k%32)/8)*16 + r%16; elem k%8
+//  PackQ  per (b,kvh): frag (vrb, kk = hd/32, plane) at (vrb*4+kk)*2+plane, virtual row vr = g*n_step + node
 //  PackK  per (b,kvh): 32-key group kb; frag (kb, c, kk) at (kb*2+c)*4+kk; key%32 = q8*8 + c*4 + i
 //                      -> lane = ((hdim%32)/8)*16 + q8*4 + i; elem hdim%8
 //  PackVt per (b,kvh): frag (kb, hb = hdim/16) at kb*8+hb; lane = ((key%32)/8)*16 + hdim%16; elem key%8
@@ -77,10 +77,18 @@ void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream
 void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
                       const float* gain, int rows, int rows_pad, int d, float eps, hipStream_t s);
 // Skinny GEMM on the matrix cores: part[s][r][n] = sum_{k in slice s} X[r][k] W[n][k], fp32.
-// rows_pad % 64 == 0, N % 16 == 0, K % 128 == 0, 1 <= splits <= K/128; returns false (nothing launched) otherwise.
+// planes = 2 uses X = hi + lo, planes = 1 only the hi plane.  rows_pad % 64 == 0, N % 16 == 0,
+// K % 128 == 0.  The plan (kernel shape + number of split-K slices) comes from bf16_gemm_plan; the
+// caller may lower plan.splits.  Returns false (nothing launched) on an unsupported shape.
+struct GemmPlan {
+  int nwn;     // 0: stream kernel (one feature group per workgroup); 2..4: wide kernel, groups per workgroup
+  int nw;      // stream kernel: wavefronts splitting the k range
+  int splits;  // split-K slices written
+};
+GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes);
 bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed,
-               int rows_pad, int N, int K, int splits, int64_t out_row_stride, hipStream_t s);
-int bf16_gemm_pick_splits(int rows_pad, int N, int K);
+               int rows_pad, int N, int K, int planes, const GemmPlan& plan, int64_t out_row_stride,
+               hipStream_t s);
 // sum partials, rotate q/k, write PackQ and the cache fragments
 void bf16_qkv_epilogue(const float* part, int n_part, int64_t part_stride, bf16_t* q_packed,
                        bf16_t* kc, bf16_t* vc, const float2* tab, const StepMeta& m,
