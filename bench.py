@@ -23,7 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
+# HBM bytes measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/*_pmc.md); None = not measured yet
+GEMM_TRAFFIC_BYTES_PER_STEP = None
+ATTN_TRAFFIC_BYTES_PER_LAUNCH = None
 
 
 def log(*a):
@@ -124,12 +127,12 @@ def attention_only_bench(di, iters=40):
     us = ms / n * 1e3
     return {"bound": "hbm", "kernel": "tree_attn_partial_kernel", "workload": "c2 attention-only",
             "achieved": alg / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+            "frac": alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": ATTN_TRAFFIC_BYTES_PER_LAUNCH,
             "us_per_launch": us, "merge_us_per_launch": ms_merge / n * 1e3, "algorithmic_bytes": alg}
 
 
-def cpu_baseline(di, wl, parent, token, budget_layers=2):
-    """The fp64 oracle on a bounded sample: the 64-row tree step of a 2-layer slice of the model
+def cpu_baseline(di, wl, parent, token, budget_layers=16):
+    """The fp64 oracle on a bounded sample: the 64-row tree step of a 16-layer slice of the model
     against a 1024-key prefix (random K/V stand in for the prefix; timing does not depend on values),
     extrapolated to the full depth: t_step = t_head + n_layers * t_layer."""
     import numpy as np
@@ -173,6 +176,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn", action="store_true")
+    ap.add_argument("--pmc-mode", action="store_true",
+                    help="for rocprofv3 --pmc runs: a 1 GiB torch copy (calibration), 2 verify steps and 2 attention-only "
+                         "launches, nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -202,6 +208,18 @@ def main():
         n = min(wl.n_nodes, P - s)
         ver.verify_step([s], [di.chain_tree(n)], [prefix[s:s + n]])
         ver.accept(mode=1)
+    if args.pmc_mode:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)  # calibration: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        for _ in range(2):
+            ver.verify_step([P], [parent], [token])
+            ver.accept(mode=0)
+        ver.close()
+        attention_only_bench(di, iters=2)
+        print(json.dumps({"pmc_mode": True}))
+        return
     planted = planted_trees(di, ver, wl, prefix, parent, token, seed=1)
 
     # headline: planted acceptance (kernel time does not depend on the acceptance length)
@@ -237,7 +255,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f16 matrix-core operands (bf16 weights widened exactly, hi/lo activation pairs), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": "c3: Llama-2-7B shape, bf16 random init N(0,0.02), prefix 1024 (Zipf 1.1), "
                                "64-node tri-gram-seeded tree of depth 6, batch 1"
@@ -249,9 +267,9 @@ def main():
         "raw_trigram_tree": {"steps_per_s": raw_steps / dt_raw, "verified_tokens_per_s": n_tok_raw / dt_raw,
                              "mean_accepted_per_step": n_tok_raw / raw_steps},
         "kernel_ms_per_step": kernels_ms,
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel (all projection GEMMs of a step)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_wide_kernel + gemm_stream_kernel (all projection GEMMs of a step)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "launches_per_step": int(gemm_launches),
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_STEP, "launches_per_step": int(gemm_launches),
                      "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                      "algorithmic_bytes_per_step": w_bytes, "mfma_tflops": gemm_tflops,
                      "mfma_frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},

@@ -471,8 +471,8 @@ int forward_bf16(ded_ctx* c) {
   bool ok = true;
   // planes: 2 = the input is consumed as hi + lo, 1 = hi only (enough for the O and down projections)
   auto gemm = [&](int cls, const bf16_t* xp, const void* w, int N, int K, int planes, int* splits_out) {
-    GemmPlan plan = bf16_gemm_plan(rows_pad, N, K, planes);
-    while (plan.splits > 1 && (int64_t)plan.splits * rows_pad * N > c->part_elems) --plan.splits;
+    int cap = (int)std::min<int64_t>(8, c->part_elems / ((int64_t)rows_pad * N));
+    GemmPlan plan = bf16_gemm_plan(rows_pad, N, K, planes, std::max(cap, 1));
     ProfScope p(c, cls);
     ok = bf16_gemm(c->part, (int64_t)rows_pad * N, xp, (const bf16_t*)w, rows_pad, N, K, planes, plan, N, s) && ok;
     *splits_out = plan.splits;
@@ -503,9 +503,7 @@ int forward_bf16(ded_ctx* c) {
   { ProfScope p(c, KC_RMSNORM);
     bf16_add_rmsnorm(c->x, c->part, S_prev, (int64_t)rows_pad * d, c->y_p, c->final_norm, m.rows, rows_pad, d, md.eps, s); }
   { ProfScope p(c, KC_GEMM_LM_HEAD);
-    GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, 2);
-    plan.splits = 1;  // the logits are written in place
-    plan.nw = 4;
+    GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, 2, /*max_splits=*/1);  // the logits are written in place
     ok = bf16_gemm(c->logits, 0, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 2, plan, md.V, s) && ok; }
   if (!ok) return DED_EINVAL;
   return launch_status();

@@ -85,7 +85,7 @@ struct GemmPlan {
   int nw;      // stream kernel: wavefronts splitting the k range
   int splits;  // split-K slices written
 };
-GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes);
+GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits = 8);
 bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed,
                int rows_pad, int N, int K, int planes, const GemmPlan& plan, int64_t out_row_stride,
                hipStream_t s);

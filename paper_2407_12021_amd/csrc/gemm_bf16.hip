@@ -343,7 +343,7 @@ double shape_cost(int64_t w_bytes, int64_t slice_bytes, int wgs, double x_per_w,
 
 }  // namespace
 
-GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes) {
+GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) {
   static const Tune tune;
   const int NG = (N + 16 * TN - 1) / (16 * TN), groups = K / (32 * PD), rg = rows_pad / 64;
   const int64_t w_bytes = (int64_t)NG * 64 * K * 2, slice = (int64_t)rows_pad * N * 4;
@@ -352,8 +352,8 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes) {
   for (int nwn = 0; nwn <= 4; ++nwn) {
     if (tune.nwn >= 0 && nwn != tune.nwn) continue;
     if (nwn == 1) continue;  // a 1-wide tile is the stream kernel
-    for (int s = 1; s <= 8 && s <= groups; ++s) {
-      if (tune.nwn >= 0 && s != std::min(tune.splits, groups)) continue;
+    for (int s = 1; s <= 8 && s <= groups && s <= max_splits; ++s) {
+      if (tune.nwn >= 0 && max_splits > 1 && s != std::min(tune.splits, groups)) continue;
       GemmPlan p{nwn, 1, s};
       double x_per_w;
       int wgs;
