@@ -28,6 +28,15 @@ constexpr int TILE = 64;         // keys per tile
 constexpr int TILE_U4 = 1024;    // uint4 units of one K (or V) tile: 64 keys * 128 dims * 2 B / 16
 constexpr float NEG_BIG = -1.0e30f;
 
+#ifdef DED_ATTN_TRACE
+__device__ unsigned long long* g_atrace = nullptr;  // [workgroup][4] wall-clock stamps (debug builds only)
+#define DED_ASTAMP(i)                                                                                         \
+  if (g_atrace && threadIdx.x == 0)                                                                           \
+    g_atrace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (i)] = wall_clock64();
+#else
+#define DED_ASTAMP(i)
+#endif
+
 __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     const uint4* __restrict__ qp, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
     float* __restrict__ part_o, float2* __restrict__ part_ml, const uint64_t* __restrict__ mask,
@@ -40,8 +49,12 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   const int G = H / Hkv;
   const int P = seq_p[b], N = seq_n[b], T = P + N;
   const int n_tiles = (T + TILE - 1) / TILE;
-  const int t_begin = (int)((int64_t)split * n_tiles / n_splits);
-  const int t_end = (int)((int64_t)(split + 1) * n_tiles / n_splits);
+  // key ranges of equal cost: a tile that holds tree keys (mask work) counts as two prefix tiles
+  const int n_plain = P / TILE;  // tiles entirely inside the prefix
+  const int cost_total = n_plain + 2 * (n_tiles - n_plain);
+  auto tile_at_cost = [&](int c) { return c <= n_plain ? c : n_plain + (c - n_plain + 1) / 2; };
+  const int t_begin = tile_at_cost((int)((int64_t)split * cost_total / n_splits));
+  const int t_end = split + 1 == n_splits ? n_tiles : tile_at_cost((int)((int64_t)(split + 1) * cost_total / n_splits));
   const int VR = G * n_step;
   const int vrb = row_tile * 4 + wave;
   const bool active = vrb * 16 < VR;  // wavefront owns real rows
@@ -49,7 +62,9 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   const int quad = lane >> 4;
   const int g = active ? vr / n_step : 0;
   const int node = active ? vr - g * n_step : 0;
+  // this lane's row of the ancestor bitmask (4 words cover 256 tree slots), kept in registers
   const uint64_t* mrow = mask + ((int64_t)b * n_step + node) * 4;
+  const uint64_t mw0 = mrow[0], mw1 = mrow[1], mw2 = mrow[2], mw3 = mrow[3];
 
   f16x8_t q[8];  // [head-dim chunk kk][plane hi / lo]
   if (active) {
@@ -135,11 +150,10 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           int key = key0 + kb * 32 + quad * 8 + j;
-          bool vis = key < P;
-          if (!vis && key < T) {
-            int tt = key - P;
-            vis = (mrow[tt >> 6] >> (tt & 63)) & 1ull;
-          }
+          const int tt = key - P;  // tree slot of this key (negative inside the prefix)
+          const int wi = tt >> 6;
+          const uint64_t word = wi == 0 ? mw0 : wi == 1 ? mw1 : wi == 2 ? mw2 : mw3;
+          const bool vis = (key < P) | ((key < T) & (bool)((word >> (tt & 63)) & 1ull));  // no short circuit: no branches
           float v = vis ? s[kb][j >> 2][j & 3] * scale_log2e : NEG_BIG;
           p[kb][j] = v;
           mx = fmaxf(mx, v);
@@ -176,9 +190,11 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
       }
   };
 
+  DED_ASTAMP(0)
   if (t_begin < t_end) {
     store_tile(0, load_tile(t_begin));
     __syncthreads();
+    DED_ASTAMP(1)
     int buf = 0;
     for (int t = t_begin; t < t_end; ++t) {
       // the last iteration re-fetches its own tile (in bounds, L2 hit) so that the loop body is branch free
@@ -191,6 +207,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     }
   }
 
+  DED_ASTAMP(2)
   if (active) {
     float l = l_run;
     l += __shfl_xor(l, 16);
@@ -203,6 +220,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
       *reinterpret_cast<float4*>(po + hb * 16) = make_float4(o[hb][0], o[hb][1], o[hb][2], o[hb][3]);
     if (quad == 0) part_ml[prow] = make_float2(m_run, l);
   }
+  DED_ASTAMP(3)
 }
 
 // One workgroup of 128 threads per (row, query head): thread = head dim.
@@ -236,7 +254,7 @@ int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int
   const int tiles = (max_p + m.n_step + TILE - 1) / TILE;
   const int base = m.batch * md.Hkv * row_tiles;
   int ns = std::max(1, 512 / std::max(base, 1));
-  ns = std::min(ns, std::max(1, tiles / 4));  // keep >= 4 tiles (256 keys) per range
+  ns = std::min(ns, std::max(1, tiles / 2));  // keep >= 2 tiles (128 keys) per range
   while (ns > 1 && (int64_t)m.batch * md.H * ns * m.n_step > part_rows_cap) --ns;
   return ns;
 }
