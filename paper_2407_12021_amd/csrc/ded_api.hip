@@ -16,6 +16,7 @@ namespace {
 constexpr int kMaskWords = 4;   // ancestor bitmask words per row (max_nodes <= 256)
 constexpr int kMaxNodes = 256;
 constexpr int64_t kAttnPartRows = 1 << 17;  // split-KV partial rows the workspace reserves at least
+constexpr int kGemmCounters = 1 << 16;      // split-K arrival tickets (a GEMM with more output tiles runs unsplit)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
@@ -74,6 +75,8 @@ struct ded_ctx {
   bf16_t *y_p = nullptr, *o_p = nullptr, *h_p = nullptr, *q_p = nullptr;
   float* part = nullptr;
   int64_t part_elems = 0;
+  float* ssq = nullptr;     // [rows_pad][d / 64] sum of squares of the residual stream per feature group
+  int* counters = nullptr;  // split-K arrival tickets, one per output tile (kept at zero between launches)
   float* attn_part_o = nullptr;
   float2* attn_part_ml = nullptr;
   int64_t attn_part_rows = 0;
@@ -238,9 +241,11 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
     bf16_t* h = w.take<bf16_t>((int64_t)z.max_rows_pad * std::max<int64_t>(F, 1) * 2);
     bf16_t* q = w.take<bf16_t>((int64_t)z.max_rows_pad * qd * 2);
     // split-K partials: at most 8 slices of 64 rows, or one slice of every row
-    int64_t widest = std::max<int64_t>(std::max<int64_t>(qkv_n, 2 * F), d);
+    int64_t widest = std::max<int64_t>(std::max<int64_t>(qkv_n, 2 * F), std::max<int64_t>(d, round_up((int)V, 64)));
     int64_t part_elems = widest * std::max<int64_t>(8 * 64, z.max_rows_pad);
     float* part = w.take<float>(part_elems);
+    float* ssq = w.take<float>((int64_t)z.max_rows_pad * (d / 64));
+    int* counters = w.take<int>(kGemmCounters);
     int64_t arows = std::max<int64_t>(kAttnPartRows, (int64_t)z.max_rows * c.n_heads);
     float* apo = w.take<float>(arows * c.head_dim);
     float2* apm = w.take<float2>(arows);
@@ -251,6 +256,8 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
       ctx->q_p = q;
       ctx->part = part;
       ctx->part_elems = part_elems;
+      ctx->ssq = ssq;
+      ctx->counters = counters;
       ctx->attn_part_o = apo;
       ctx->attn_part_ml = apm;
       ctx->attn_part_rows = arows;
@@ -466,45 +473,89 @@ int forward_bf16(ded_ctx* c) {
   const ModelDims& md = c->md;
   StepMeta m = c->meta();
   hipStream_t s = c->stream;
-  const int d = md.d, qd = md.H * md.hd, kvd = md.Hkv * md.hd, qkv_n = qd + 2 * kvd, F = md.F;
+  const int d = md.d, qd = md.H * md.hd, kvd = md.Hkv * md.hd, qkv_n = qd + 2 * kvd, F = md.F, L = md.n_layers;
   const int rows_pad = round_up(m.rows, 64);
   bool ok = true;
+  GemmEpilogue base = {};
+  base.rows = m.rows;
+  base.rb_total = rows_pad / 16;
+  base.eps = md.eps;
   // planes: 2 = the input is consumed as hi + lo, 1 = hi only (enough for the O and down projections)
-  auto gemm = [&](int cls, const bf16_t* xp, const void* w, int N, int K, int planes, int* splits_out) {
-    int cap = (int)std::min<int64_t>(8, c->part_elems / ((int64_t)rows_pad * N));
+  auto gemm = [&](int cls, const bf16_t* xp, const void* w, int N, int K, int planes, const GemmEpilogue& epi) {
+    const int64_t slice = (int64_t)rows_pad * round_up(N, 64);
+    int cap = (int)std::min<int64_t>(8, c->part_elems / slice);
     GemmPlan plan = bf16_gemm_plan(rows_pad, N, K, planes, std::max(cap, 1));
+    if (bf16_gemm_tiles(rows_pad, N, plan) > kGemmCounters) plan.splits = 1;
     ProfScope p(c, cls);
-    ok = bf16_gemm(c->part, (int64_t)rows_pad * N, xp, (const bf16_t*)w, rows_pad, N, K, planes, plan, N, s) && ok;
-    *splits_out = plan.splits;
+    ok = bf16_gemm(c->part, slice, xp, (const bf16_t*)w, rows_pad, N, K, planes, plan, c->counters,
+                   epi, s) && ok;
   };
+  // RMSNorm is deferred: whoever produces the residual stream also writes x * gain(next norm) as the next
+  // GEMM input and sum(x^2) per 64 features; the consuming GEMM multiplies its output rows by 1/rms.
+  auto normed_input = [&](GemmEpilogue& e) {
+    e.ssq_in = c->ssq;
+    e.ssq_groups = d / 64;
+    e.inv_k = 1.0f / (float)d;
+  };
+  auto next_gain = [&](int l) { return l < L ? c->norm_attn[l] : c->final_norm; };
   { ProfScope p(c, KC_ROPE_TABLE); launch_rope_table(c->rope_tab, m.pos, m.rows, md.hd, md.rope_base, s); }
-  { ProfScope p(c, KC_EMBED); bf16_embed(c->x, (const bf16_t*)c->emb, m, d, s); }
-  int S_prev = 0;  // partial slices waiting to be added to the residual stream
-  for (int l = 0; l < md.n_layers; ++l) {
-    { ProfScope p(c, KC_RMSNORM);
-      bf16_add_rmsnorm(c->x, c->part, S_prev, (int64_t)rows_pad * d, c->y_p, c->norm_attn[l], m.rows, rows_pad, d, md.eps, s); }
-    int S = 1;
-    gemm(KC_GEMM_QKV, c->y_p, c->wqkv[l], qkv_n, d, 2, &S);
-    { ProfScope p(c, KC_QKV_EPILOGUE);
-      bf16_qkv_epilogue(c->part, S, (int64_t)rows_pad * qkv_n, c->q_p, (bf16_t*)c->kc[l], (bf16_t*)c->vc[l], c->rope_tab, m, md, s); }
+  { ProfScope p(c, KC_EMBED); bf16_embed(c->x, c->y_p, c->ssq, (const bf16_t*)c->emb, next_gain(0), m, rows_pad, d, s); }
+  for (int l = 0; l < L; ++l) {
+    {
+      GemmEpilogue e = base;
+      e.kind = EPI_QKV;
+      normed_input(e);
+      e.q_packed = c->q_p;
+      e.k_cache = (bf16_t*)c->kc[l];
+      e.v_cache = (bf16_t*)c->vc[l];
+      e.rope_tab = c->rope_tab;
+      e.seq_p = m.seq_p;
+      e.seq_n = m.seq_n;
+      e.n_step = m.n_step;
+      e.H = md.H;
+      e.Hkv = md.Hkv;
+      e.cap = md.cap;
+      gemm(KC_GEMM_QKV, c->y_p, c->wqkv[l], qkv_n, d, 2, e);
+    }
     int ns = bf16_attn_pick_splits(m, md, c->max_p, c->attn_part_rows);
     { ProfScope p(c, KC_TREE_ATTN);
       bf16_tree_attention_partial(c->q_p, (const bf16_t*)c->kc[l], (const bf16_t*)c->vc[l], c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
     { ProfScope p(c, KC_ATTN_MERGE);
       bf16_tree_attention_merge(c->o_p, rows_pad, c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
-    gemm(KC_GEMM_O, c->o_p, c->wo[l], d, qd, 1, &S);
-    { ProfScope p(c, KC_RMSNORM);
-      bf16_add_rmsnorm(c->x, c->part, S, (int64_t)rows_pad * d, c->y_p, c->norm_ffn[l], m.rows, rows_pad, d, md.eps, s); }
-    gemm(KC_GEMM_GATE_UP, c->y_p, c->wgu[l], 2 * F, d, 2, &S);
-    { ProfScope p(c, KC_SILU_MUL);
-      bf16_silu_mul(c->h_p, c->part, S, (int64_t)rows_pad * 2 * F, m.rows, rows_pad, F, s); }
-    gemm(KC_GEMM_DOWN, c->h_p, c->wdown[l], d, F, 1, &S_prev);
+    {
+      GemmEpilogue e = base;
+      e.kind = EPI_RESIDUAL;
+      e.x = c->x;
+      e.gain = c->norm_ffn[l];
+      e.y_packed = c->y_p;
+      e.ssq_out = c->ssq;
+      gemm(KC_GEMM_O, c->o_p, c->wo[l], d, qd, 1, e);
+    }
+    {
+      GemmEpilogue e = base;
+      e.kind = EPI_SILU;
+      normed_input(e);
+      e.y_packed = c->h_p;
+      gemm(KC_GEMM_GATE_UP, c->y_p, c->wgu[l], 2 * F, d, 2, e);
+    }
+    {
+      GemmEpilogue e = base;
+      e.kind = EPI_RESIDUAL;
+      e.x = c->x;
+      e.gain = next_gain(l + 1);
+      e.y_packed = c->y_p;
+      e.ssq_out = c->ssq;
+      gemm(KC_GEMM_DOWN, c->h_p, c->wdown[l], d, F, 1, e);
+    }
   }
-  { ProfScope p(c, KC_RMSNORM);
-    bf16_add_rmsnorm(c->x, c->part, S_prev, (int64_t)rows_pad * d, c->y_p, c->final_norm, m.rows, rows_pad, d, md.eps, s); }
-  { ProfScope p(c, KC_GEMM_LM_HEAD);
-    GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, 2, /*max_splits=*/1);  // the logits are written in place
-    ok = bf16_gemm(c->logits, 0, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 2, plan, md.V, s) && ok; }
+  {
+    GemmEpilogue e = base;
+    e.kind = EPI_LOGITS;
+    normed_input(e);
+    e.out = c->logits;
+    e.out_stride = md.V;
+    gemm(KC_GEMM_LM_HEAD, c->y_p, c->lm_head, md.V, d, 2, e);
+  }
   if (!ok) return DED_EINVAL;
   return launch_status();
 }
@@ -635,12 +686,12 @@ int ded_verify_init(const ded_config* cfg, const ded_weights* w, const ded_kv* k
       INIT_TRY(copy_gain(c->norm_ffn[l], w->norm_ffn[l]));
     }
   } else {
-    bf16_pack_weight((bf16_t*)c->lm_head, (const bf16_t*)w->lm_head, (int)V, (int)d, s);
+    bf16_pack_weight((bf16_t*)c->lm_head, (const bf16_t*)w->lm_head, (int)V, (int)d, PERM_NONE, s);
     for (int l = 0; l < L; ++l) {
-      bf16_pack_weight((bf16_t*)c->wqkv[l], (const bf16_t*)w->wqkv[l], (int)qkv_n, (int)d, s);
-      bf16_pack_weight((bf16_t*)c->wo[l], (const bf16_t*)w->wo[l], (int)d, (int)qd, s);
-      bf16_pack_weight((bf16_t*)c->wgu[l], (const bf16_t*)w->wgate_up[l], (int)(2 * F), (int)d, s);
-      bf16_pack_weight((bf16_t*)c->wdown[l], (const bf16_t*)w->wdown[l], (int)d, (int)F, s);
+      bf16_pack_weight((bf16_t*)c->wqkv[l], (const bf16_t*)w->wqkv[l], (int)qkv_n, (int)d, PERM_ROPE, s);
+      bf16_pack_weight((bf16_t*)c->wo[l], (const bf16_t*)w->wo[l], (int)d, (int)qd, PERM_NONE, s);
+      bf16_pack_weight((bf16_t*)c->wgu[l], (const bf16_t*)w->wgate_up[l], (int)(2 * F), (int)d, PERM_GATE_UP, s);
+      bf16_pack_weight((bf16_t*)c->wdown[l], (const bf16_t*)w->wdown[l], (int)d, (int)F, PERM_NONE, s);
       INIT_TRY(copy_gain(c->norm_attn[l], w->norm_attn[l]));
       INIT_TRY(copy_gain(c->norm_ffn[l], w->norm_ffn[l]));
     }

@@ -71,28 +71,54 @@ void f32_gather_rows(float* dst, const float* src, const StepMeta& m, int max_no
 //  PackVt per (b,kvh): frag (kb, hb = hdim/16) at kb*8+hb; lane = ((key%32)/8)*16 + hdim%16; elem key%8
 typedef uint16_t bf16_t;
 
-void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, hipStream_t s);
-void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream_t s);
-// x[r] += sum_s part[s][r] (n_part may be 0); y = PackX(bf16(rmsnorm(x) * gain))
-void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
-                      const float* gain, int rows, int rows_pad, int d, float eps, hipStream_t s);
-// Skinny GEMM on the matrix cores: part[s][r][n] = sum_{k in slice s} X[r][k] W[n][k], fp32.
-// planes = 2 uses X = hi + lo, planes = 1 only the hi plane.  rows_pad % 64 == 0, N % 16 == 0,
-// K % 128 == 0.  The plan (kernel shape + number of split-K slices) comes from bf16_gemm_plan; the
-// caller may lower plan.splits.  Returns false (nothing launched) on an unsupported shape.
+// How the features (rows) of a weight matrix are ordered inside PackW.  The paired orders put partner
+// features into tiles t and t + 2 of one 64-feature group so that one wavefront holds both.
+enum { PERM_NONE = 0, PERM_ROPE = 1 /* per head: dims i and i + 64 */, PERM_GATE_UP = 2 /* gate f and up f */ };
+void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, int perm, hipStream_t s);
+// x = emb[token]; y = (x * gain) as hi/lo f16 in PackX; ssq[r][g] = sum of x^2 over feature group g (64 wide)
+void bf16_embed(float* x, bf16_t* y_packed, float* ssq, const bf16_t* emb, const float* gain, const StepMeta& m,
+                int rows_pad, int d, hipStream_t s);
+
+// What a GEMM does with its result tile (fused epilogue).  RMSNorm is deferred: producers write
+// x * gain and sum(x^2) per 64-feature group, consumers multiply their output rows by 1/rms.
+enum { EPI_LOGITS = 0, EPI_QKV = 1, EPI_SILU = 2, EPI_RESIDUAL = 3 };
+struct GemmEpilogue {
+  int kind;
+  // row scale of the GEMM input (null: 1): scale[r] = rsqrt(sum_g ssq_in[r][g] * inv_k + eps)
+  const float* ssq_in;
+  int ssq_groups;
+  float inv_k, eps;
+  int rows;      // real rows (the rest up to rows_pad is padding)
+  int rb_total;  // rows_pad / 16 of the PackX buffers
+  // EPI_LOGITS: out[r][n] = scale * Y
+  float* out;
+  int64_t out_stride;
+  // EPI_QKV: rotary embedding at the row's position, queries -> PackQ (hi/lo), keys / values -> cache
+  bf16_t *q_packed, *k_cache, *v_cache;
+  const float2* rope_tab;
+  const int32_t *seq_p, *seq_n;
+  int n_step, H, Hkv, cap;
+  // EPI_SILU: y_packed(hi) = silu(scale*gate) * (scale*up);  EPI_RESIDUAL: x += Y, y_packed = x*gain (hi/lo), ssq_out
+  bf16_t* y_packed;
+  float* x;
+  const float* gain;
+  float* ssq_out;
+};
+
+// Skinny GEMM on the matrix cores with a fused epilogue.  planes = 2 uses X = hi + lo, planes = 1 only the
+// hi plane.  rows_pad % 64 == 0, N % 16 == 0 (N % 64 for the paired epilogues), K % 128 == 0.  `part` holds
+// plan.splits slices of part_stride >= rows_pad * round_up(N, 64) floats, `counters` one zeroed int per output tile (left zeroed).
+// Returns false (nothing launched) on an unsupported shape.
 struct GemmPlan {
   int nwn;     // 0: stream kernel (one feature group per workgroup); 2..4: wide kernel, groups per workgroup
   int nw;      // stream kernel: wavefronts splitting the k range
-  int splits;  // split-K slices written
+  int splits;  // split-K slices
 };
 GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits = 8);
-bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed,
-               int rows_pad, int N, int K, int planes, const GemmPlan& plan, int64_t out_row_stride,
+int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan);
+bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed, int rows_pad,
+               int N, int K, int planes, const GemmPlan& plan, int* counters, const GemmEpilogue& epi,
                hipStream_t s);
-// sum partials, rotate q/k, write PackQ and the cache fragments
-void bf16_qkv_epilogue(const float* part, int n_part, int64_t part_stride, bf16_t* q_packed,
-                       bf16_t* kc, bf16_t* vc, const float2* tab, const StepMeta& m,
-                       const ModelDims& md, hipStream_t s);
 // Tree-masked attention, two launches: split-KV partials (running max, sum, unnormalised output per
 // key range), then the merge that writes PackX(o).  n_splits from bf16_attn_pick_splits.
 // part_o: [B][H][n_splits][n_step][hd] fp32, part_ml: [B][H][n_splits][n_step] float2 (max, sum).
@@ -102,8 +128,6 @@ void bf16_tree_attention_partial(const bf16_t* q_packed, const bf16_t* kc, const
                                  hipStream_t s);
 void bf16_tree_attention_merge(bf16_t* o_packed, int rows_pad, const float* part_o, const float2* part_ml,
                                int n_splits, const StepMeta& m, const ModelDims& md, hipStream_t s);
-void bf16_silu_mul(bf16_t* h_packed, const float* part, int n_part, int64_t part_stride, int rows,
-                   int rows_pad, int F, hipStream_t s);
 void bf16_kv_compact(bf16_t* const* kc, bf16_t* const* vc, const int32_t* path, const int32_t* n_acc,
                      const StepMeta& m, const ModelDims& md, int stride, hipStream_t s);
 void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_plain, bool to_cache,

@@ -1,23 +1,27 @@
-// Skinny 16-bit GEMM on the CDNA matrix cores: Y[r][n] = sum_k X[r][k] W[n][k] for a few tens of rows.
+// Skinny 16-bit GEMM on the CDNA matrix cores with fused epilogues:
+//   Y[r][n] = sum_k X[r][k] W[n][k] for a few tens of rows, followed in the same kernel by what the
+//   decoder does with Y (rotary embedding + cache append, SiLU*up, residual add + next input, logits).
 //
 // At tree sizes (R <= 64 rows) the projection is bound by streaming the weights from HBM once.  What
 // was measured on MI355X and shaped these kernels:
 //   * plain 16-byte-per-lane streaming tops out near 6.2 TB/s for the chip and near 52 GB/s per CU,
 //     so every CU has to stream its equal share (~24 GB/s) for the whole kernel, and whatever else a
 //     CU loads (the activations) comes out of the same per-CU budget, even when it hits in L2;
-//   * a wavefront that reads one contiguous stream is ~15 % faster than one that interleaves four.
+//   * a wavefront that reads one contiguous stream is ~15 % faster than one that interleaves four;
+//   * every launch costs ~3.5 us even back-to-back, and a small dependent kernel 6-10 us, which is
+//     why the split-K reduction and the element-wise stages live in the GEMM's epilogue.
 // Hence:
 //   * weights are pre-laid-out (PackW, f16) as MFMA A-operand fragments in the order a wavefront
 //     consumes them: 64-feature group -> k step -> 4 feature tiles -> lane; one k step of a group is
 //     4 KiB of contiguous memory fetched by four coalesced 1 KiB loads straight into registers;
 //   * activations (PackX, B operand, hi/lo f16 planes) are shared: in the "wide" kernel the NWN
-//     wavefronts of a workgroup own NWN neighbouring feature groups over the same k range and the
-//     activation chunks go through LDS once per workgroup (double buffered, one barrier per chunk);
-//   * narrow outputs (few feature groups) use the "stream" kernel instead: one feature group per
-//     workgroup, the NW wavefronts split the k range and combine through LDS in a fixed tree order;
-//   * blockIdx.y is a global split-K whose slices are written separately and summed in slice order
-//     by the consumer kernel (no atomics -> bit-reproducible); the planner picks the shape whose
-//     workgroup count fills the 256 CUs most evenly with the least extra traffic.
+//     wavefronts of a half-workgroup own NWN neighbouring feature groups over the same k range and
+//     the activation chunks go through LDS once (double buffered, one barrier per chunk);
+//   * narrow outputs use the "stream" kernel: one feature group per workgroup, the NW wavefronts
+//     split the k range and combine through LDS in a fixed tree order;
+//   * blockIdx.y is a global split-K.  Every slice is written to its own buffer; the workgroup that
+//     finishes LAST for an output tile (atomic ticket, device-coherent slice accesses, no waiting) re-reads all
+//     slices IN SLICE ORDER and runs the epilogue, so the result does not depend on arrival order.
 // v_mfma_f32_16x16x32_f16: A = weights (M = 16 features), B = activations (N = 16 rows),
 // C[m][n] lands in lane (n + 16*(m/4)), element m%4: four consecutive features of one row.
 // X = hi + lo (two planes): both products accumulate into the same fp32 registers.
@@ -37,40 +41,253 @@ constexpr int PD = 4;            // k steps (of 32) per group of the k-range spl
 constexpr int RING = 2;          // k steps in flight per wavefront (stream kernel)
 
 #ifdef DED_GEMM_TRACE
-__device__ unsigned long long* g_trace = nullptr;  // [workgroup][wave][4] wall-clock stamps (debug builds only)
+__device__ unsigned long long* g_trace = nullptr;  // [workgroup][wave][8] wall-clock stamps (debug builds only)
 #define DED_STAMP(i)                                                                                       \
   if (g_trace && (threadIdx.x & 63) == 0)                                                                  \
-    g_trace[((((size_t)blockIdx.y * gridDim.x + blockIdx.x) * (blockDim.x >> 6)) + (threadIdx.x >> 6)) * 4 + (i)] = \
+    g_trace[((((size_t)blockIdx.y * gridDim.x + blockIdx.x) * (blockDim.x >> 6)) + (threadIdx.x >> 6)) * 8 + (i)] = \
         wall_clock64();
 #else
 #define DED_STAMP(i)
 #endif
 
-__device__ inline void store_tile(float* out, int64_t out_row_stride, int ng, int N, int rb0, int lane,
-                                  const f32x4_t (&acc)[TN][4]) {
-  const int row_in = lane & 15, quad = lane >> 4;
+typedef f32x4_t Acc[TN][4];  // one wavefront's tile: 4 feature tiles x 4 row blocks
+
+// Split-K slices travel between workgroups of one launch, which may sit on different XCDs with separate
+// L2 caches.  Instead of device-scope fences (a whole-L2 write-back and invalidate per workgroup, measured
+// at 3-4x the kernel time) the slices are written and read with device-scope relaxed atomic accesses, which
+// go through to the memory side on their own; ordering comes from waiting for the stores to complete
+// before the ticket is taken, and from the ticket's return value before the loads are issued.
+// A slice is private to the kernel, so it is kept in accumulator order: tile (row group, feature group) ->
+// (t, rb) -> half -> lane, 8 bytes each: every store / load instruction covers 512 contiguous bytes.
+__device__ inline unsigned long long pack2(float a, float b) {
+  return ((unsigned long long)__float_as_uint(b) << 32) | __float_as_uint(a);
+}
+__device__ inline int64_t slice_tile_offset(int rb0, int NG, int ng) { return ((int64_t)(rb0 >> 2) * NG + ng) * (TN * 4 * 256); }
+
+__device__ inline void store_slice(float* slice, int NG, int ng, int rb0, int lane, const Acc& acc) {
+  unsigned long long* q = reinterpret_cast<unsigned long long*>(slice + slice_tile_offset(rb0, NG, ng)) + lane;
 #pragma unroll
-  for (int t = 0; t < TN; ++t) {
-    const int n = (ng * TN + t) * 16 + quad * 4;
-    if (n >= N) continue;  // ragged last group (N % 64 != 0): padded features are dropped
+  for (int t = 0; t < TN; ++t)
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
-      const int64_t r = (int64_t)(rb0 + rb) * 16 + row_in;
-      f32x4_t v = acc[t][rb];
-      *reinterpret_cast<float4*>(out + r * out_row_stride + n) = make_float4(v[0], v[1], v[2], v[3]);
+      const f32x4_t v = acc[t][rb];
+      __hip_atomic_store(q + (t * 4 + rb) * 128, pack2(v[0], v[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(q + (t * 4 + rb) * 128 + 64, pack2(v[2], v[3]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// acc[t][j] = sum over slices 0..splits-1 (in slice order) of row block rb_lo + j of the tile, j < RBN
+template <int RBN>
+__device__ inline void load_slices(const float* part, int64_t part_stride, int splits, int NG, int ng, int rb0,
+                                   int rb_lo, int lane, Acc& acc) {
+#pragma unroll
+  for (int t = 0; t < TN; ++t)
+#pragma unroll
+    for (int j = 0; j < RBN; ++j) acc[t][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const float* base = part + slice_tile_offset(rb0, NG, ng) + rb_lo * 256;
+#pragma unroll 4
+  for (int s = 0; s < splits; ++s) {
+    unsigned long long* q =
+        reinterpret_cast<unsigned long long*>(const_cast<float*>(base) + (int64_t)s * part_stride) + lane;
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+      for (int j = 0; j < RBN; ++j) {
+        unsigned long long a = __hip_atomic_load(q + (t * 4 + j) * 128, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long b = __hip_atomic_load(q + (t * 4 + j) * 128 + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        acc[t][j] += f32x4_t{__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)),
+                             __uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32))};
+      }
+  }
+}
+
+__device__ inline uint2 pack4_f16(float a, float b, float c, float d) {
+  return make_uint2((uint32_t)f32_to_f16(a) | ((uint32_t)f32_to_f16(b) << 16),
+                    (uint32_t)f32_to_f16(c) | ((uint32_t)f32_to_f16(d) << 16));
+}
+__device__ inline void split4_f16(const float (&v)[4], uint2& hi, uint2& lo) {
+  uint16_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_f16(v[i], h[i], l[i]);
+  hi = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+  lo = make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+}
+
+// ------------------------------------------------------------------------------------------
+// Epilogues.  Run by one wavefront on RBN row blocks (first one: rbase) of a 64-feature group; acc[t][j]
+// holds row block rbase + j.  A lane holds, for row (rbase + j) * 16 + (lane & 15), the 4 features
+// t * 16 + (lane >> 4) * 4 + i.  Feature groups of the QKV and gate/up matrices are interleaved at pack
+// time (packw_source_row) so that tiles t and t + 2 of a group hold partner features: rotary pairs
+// (i, i + 64), or gate / up.
+// ------------------------------------------------------------------------------------------
+// RMSNorm scale of row rb0 * 16 + lane of the GEMM input (the producer stored sum(x^2) per 64-feature group).
+// Fetched right after the first weight loads are issued, as one batch of independent loads, so that neither
+// the main loop nor the epilogue waits for it.
+__device__ inline float input_row_scale(const GemmEpilogue& e, int rb0, int lane) {
+  if (!e.ssq_in) return 1.f;
+  const float2* p = reinterpret_cast<const float2*>(e.ssq_in + (int64_t)(rb0 * 16 + lane) * e.ssq_groups);
+  float s = 0.f;
+#pragma unroll 32
+  for (int g = 0; g < e.ssq_groups / 2; ++g) {
+    float2 v = p[g];
+    s += v.x + v.y;
+  }
+  return 1.0f / sqrtf(s * e.inv_k + e.eps);
+}
+
+template <int EPI, int RBN>
+__device__ inline void run_epilogue(const GemmEpilogue& e, int ng, int N, int rb0, int rbase, float row_scale, int lane,
+                                    Acc& acc) {
+  const int row_in = lane & 15, quad = lane >> 4;
+  float scale[RBN];
+#pragma unroll
+  for (int j = 0; j < RBN; ++j) scale[j] = __shfl(row_scale, (rbase - rb0 + j) * 16 + row_in);
+
+  if (EPI == EPI_LOGITS) {
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+      const int n = (ng * TN + t) * 16 + quad * 4;
+      if (n >= N) continue;
+#pragma unroll
+      for (int rb = 0; rb < RBN; ++rb) {
+        const int64_t r = (int64_t)(rbase + rb) * 16 + row_in;
+        f32x4_t v = acc[t][rb] * scale[rb];
+        *reinterpret_cast<float4*>(e.out + r * e.out_stride + n) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  } else if (EPI == EPI_RESIDUAL) {
+    // x += Y;  next GEMM input = (x * gain) as hi/lo f16 (its 1/rms is applied by the consumer);  sum(x^2) per group
+#pragma unroll
+    for (int rb = 0; rb < RBN; ++rb) {
+      const int r = (rbase + rb) * 16 + row_in;
+      float ss = 0.f;
+#pragma unroll
+      for (int t = 0; t < TN; ++t) {
+        const int n = (ng * TN + t) * 16 + quad * 4;
+        float* xp = e.x + (int64_t)r * N + n;
+        float4 xv = *reinterpret_cast<const float4*>(xp);
+        float4 g = *reinterpret_cast<const float4*>(e.gain + n);
+        float xn[4] = {xv.x + acc[t][rb][0], xv.y + acc[t][rb][1], xv.z + acc[t][rb][2], xv.w + acc[t][rb][3]};
+        *reinterpret_cast<float4*>(xp) = make_float4(xn[0], xn[1], xn[2], xn[3]);
+        ss += xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
+        float y[4] = {xn[0] * g.x, xn[1] * g.y, xn[2] * g.z, xn[3] * g.w};
+        uint2 hi, lo;
+        split4_f16(y, hi, lo);
+        *reinterpret_cast<uint2*>(e.y_packed + packx_index(r, n, e.rb_total, 0)) = hi;
+        *reinterpret_cast<uint2*>(e.y_packed + packx_index(r, n, e.rb_total, 1)) = lo;
+      }
+      ss += __shfl_xor(ss, 16);
+      ss += __shfl_xor(ss, 32);
+      if (quad == 0) e.ssq_out[(int64_t)r * (N / 64) + ng] = ss;
+    }
+  } else if (EPI == EPI_SILU) {
+    // group ng = gate features [32 ng, 32 ng + 32) in tiles 0, 1 and the matching up features in tiles 2, 3
+#pragma unroll
+    for (int rb = 0; rb < RBN; ++rb) {
+      const int r = (rbase + rb) * 16 + row_in;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int f = ng * 32 + t * 16 + quad * 4;
+        if (2 * f >= N) continue;
+        float h[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float gv = acc[t][rb][i] * scale[rb], uv = acc[t + 2][rb][i] * scale[rb];
+          h[i] = gv / (1.0f + __expf(-gv)) * uv;
+        }
+        *reinterpret_cast<uint2*>(e.y_packed + packx_index(r, f, e.rb_total, 0)) = pack4_f16(h[0], h[1], h[2], h[3]);
+      }
+    }
+  } else if (EPI == EPI_QKV) {
+    // group ng = head slot ng / 2, dims [32 j, 32 j + 32) in tiles 0, 1 and their rotary partners (+64) in tiles 2, 3
+    const int hs = ng >> 1, j = ng & 1;
+    const int G = e.H / e.Hkv;
+#pragma unroll
+    for (int rb = 0; rb < RBN; ++rb) {
+      const int r = (rbase + rb) * 16 + row_in;
+      if (r >= e.rows) continue;
+      const int b = r / e.n_step, node = r - b * e.n_step;
+      const bool real = node < e.seq_n[b];
+      const int slot = e.seq_p[b] + node;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int d0 = 32 * j + 16 * t + quad * 4;
+        float a[4], c[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[i] = acc[t][rb][i] * scale[rb];
+          c[i] = acc[t + 2][rb][i] * scale[rb];
+        }
+        if (hs < e.H + e.Hkv) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float2 cs = e.rope_tab[(int64_t)r * 64 + d0 + i];
+            float ra = a[i] * cs.x - c[i] * cs.y;
+            float rc = c[i] * cs.x + a[i] * cs.y;
+            a[i] = ra;
+            c[i] = rc;
+          }
+        }
+        if (hs < e.H) {
+          const int kvh = hs / G, g = hs - kvh * G;
+          const int vr = g * e.n_step + node;
+          uint16_t* base = e.q_packed + ((int64_t)b * e.Hkv + kvh) * ((int64_t)G * e.n_step * 128 * 2);
+          uint2 hi, lo;
+          split4_f16(a, hi, lo);
+          *reinterpret_cast<uint2*>(base + packq_index(vr, d0, 0)) = hi;
+          *reinterpret_cast<uint2*>(base + packq_index(vr, d0, 1)) = lo;
+          split4_f16(c, hi, lo);
+          *reinterpret_cast<uint2*>(base + packq_index(vr, d0 + 64, 0)) = hi;
+          *reinterpret_cast<uint2*>(base + packq_index(vr, d0 + 64, 1)) = lo;
+        } else if (real && hs < e.H + e.Hkv) {
+          uint16_t* base = e.k_cache + ((int64_t)b * e.Hkv + (hs - e.H)) * ((int64_t)e.cap * 128);
+          *reinterpret_cast<uint2*>(base + packk_index(slot, d0)) = pack4_f16(a[0], a[1], a[2], a[3]);
+          *reinterpret_cast<uint2*>(base + packk_index(slot, d0 + 64)) = pack4_f16(c[0], c[1], c[2], c[3]);
+        } else if (real) {
+          uint16_t* base = e.v_cache + ((int64_t)b * e.Hkv + (hs - e.H - e.Hkv)) * ((int64_t)e.cap * 128);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            base[packvt_index(slot, d0 + i)] = f32_to_f16(a[i]);
+            base[packvt_index(slot, d0 + 64 + i)] = f32_to_f16(c[i]);
+          }
+        }
+      }
     }
   }
+}
+
+// Split-K hand-over (splits > 1).  The wavefronts that hold a complete workgroup tile (`owner`) write it as
+// this workgroup's slice; returns true in the workgroup that arrived last for its output tile, which then
+// re-reads all slices in slice order (load_slices, any of its wavefronts) and runs the epilogue.
+__device__ inline bool finish_split(float* part, int64_t part_stride, int split, int splits, int* counters, int NG,
+                                    int ng, int rb0, int lane, bool owner, const Acc& acc, int* s_flag) {
+  if (owner) store_slice(part + (int64_t)split * part_stride, NG, ng, rb0, lane, acc);
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): this wavefront's slice stores have completed
+  DED_STAMP(4)
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int* ticket = counters + (blockIdx.z * gridDim.x + blockIdx.x);
+    int prev = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int last = prev == splits - 1;
+    if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+    *s_flag = last;
+  }
+  __syncthreads();
+  DED_STAMP(5)
+  return *s_flag != 0;
 }
 
 // ------------------------------------------------------------------------------------------
 // Stream kernel: one feature group per workgroup, NW wavefronts split the k range.
 // ------------------------------------------------------------------------------------------
-template <int NW, int PLANES>
+template <int NW, int PLANES, int EPI>
 __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restrict__ part, int64_t part_stride,
                                                                  const uint4* __restrict__ xp,
                                                                  const uint4* __restrict__ wp, int RB, int N, int KT,
-                                                                 int splits, int64_t out_row_stride) {
+                                                                 int splits, int* __restrict__ counters,
+                                                                 GemmEpilogue epi) {
   __shared__ float4 red[(NW > 1 ? NW / 2 : 1) * TN * 4 * 64];
+  __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ng = blockIdx.x;
   const int split = blockIdx.y;
@@ -82,12 +299,14 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
   const int g_begin = (int)((int64_t)gi * groups / parts);
   const int g_end = (int)((int64_t)(gi + 1) * groups / parts);
 
-  f32x4_t acc[TN][4];
+  Acc acc;
 #pragma unroll
   for (int t = 0; t < TN; ++t)
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+  DED_STAMP(0)
+  float row_scale = 1.f;
   if (g_begin < g_end) {
     const uint4* wsrc = wp + (((int64_t)ng * KT * TN) << 6) + lane;
     // per k step the activations of the 4 row blocks x 2 planes (hi, lo) are 8 KiB of contiguous memory
@@ -120,6 +339,7 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
     const int kt_last = g_end * PD - RING;  // first step of the last ring-full (range length % RING == 0)
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j, kt + j);
+    row_scale = input_row_scale(epi, rb0, lane);
     for (; kt < kt_last; kt += RING) {
 #pragma unroll
       for (int j = 0; j < RING; ++j) {
@@ -129,8 +349,11 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
     }
 #pragma unroll
     for (int j = 0; j < RING; ++j) compute(j);
+  } else {
+    row_scale = input_row_scale(epi, rb0, lane);
   }
 
+  DED_STAMP(2)
   // combine the NW k ranges: wave w += wave w + stride, stride = NW/2 .. 1
   if (NW > 1) {
 #pragma unroll
@@ -159,7 +382,16 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
       __syncthreads();
     }
   }
-  if (wave == 0) store_tile(part + (int64_t)split * part_stride, out_row_stride, ng, N, rb0, lane, acc);
+  DED_STAMP(3)
+  if (splits == 1) {
+    if (wave == 0) run_epilogue<EPI, 4>(epi, ng, N, rb0, rb0, row_scale, lane, acc);
+  } else if (finish_split(part, part_stride, split, splits, counters, gridDim.x, ng, rb0, lane, wave == 0, acc, &s_flag)) {
+    constexpr int RBN = 4 / NW;  // the wavefronts of the last workgroup share the tile's row blocks
+    load_slices<RBN>(part, part_stride, splits, gridDim.x, ng, rb0, wave * RBN, lane, acc);
+    DED_STAMP(6)
+    run_epilogue<EPI, RBN>(epi, ng, N, rb0, rb0 + wave * RBN, row_scale, lane, acc);
+  }
+  DED_STAMP(7)
 }
 
 // ------------------------------------------------------------------------------------------
@@ -170,11 +402,12 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
 // 1/NWN of what they would if every wavefront fetched its own.  Two wavefronts per SIMD overlap each
 // other's LDS waits and barriers; the halves are added through LDS at the end (fixed order).
 // ------------------------------------------------------------------------------------------
-template <int NWN, int PLANES>
+template <int NWN, int PLANES, int EPI>
 __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restrict__ part, int64_t part_stride,
                                                                  const uint4* __restrict__ xp,
                                                                  const uint4* __restrict__ wp, int RB, int N, int KT,
-                                                                 int splits, int64_t out_row_stride) {
+                                                                 int splits, int* __restrict__ counters,
+                                                                 GemmEpilogue epi) {
   constexpr int TH = NWN * 64;                    // threads per half
   constexpr int CH = (NWN == 4 || PLANES == 1) ? 2 : 1;  // k steps per activation chunk (<= 4 staged units / thread)
   constexpr int STEP_U4 = 4 * PLANES * 64;        // uint4 units of activations per k step
@@ -183,6 +416,7 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   constexpr int ACC_U4 = TN * 4 * 64;             // float4 units of one wavefront's accumulators
   constexpr int LDS_U4 = (2 * 2 * CHUNK_U4 > NWN * ACC_U4) ? 2 * 2 * CHUNK_U4 : NWN * ACC_U4;
   __shared__ uint4 lds[LDS_U4];                   // [half][buffer][chunk]; reused for the final reduction
+  __shared__ int s_flag;
   const int half = threadIdx.x / TH;
   const int tid = threadIdx.x - half * TH, lane = tid & 63, wn = tid >> 6;
   uint4* xs = lds + half * 2 * CHUNK_U4;
@@ -197,7 +431,7 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   const int n_chunks = (g_end - g_begin) * (PD / CH) / 2;  // per half; the range holds an even number of chunks
   const int kt0 = g_begin * PD + half * n_chunks * CH;
 
-  f32x4_t acc[TN][4];
+  Acc acc;
 #pragma unroll
   for (int t = 0; t < TN; ++t)
 #pragma unroll
@@ -267,8 +501,10 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   // of the farther chunk, so that waiting for them (loads retire in order) leaves the weight loads in flight.
   // Both halves run the same number of iterations, hence the same number of barriers (n_chunks >= 2).
   WChunk w0 = load_w(0);
-  store_x(0, load_x(0));
+  XStage x0 = load_x(0);
   WChunk w1 = load_w(1);
+  const float row_scale = input_row_scale(epi, rb0, lane);
+  store_x(0, x0);
   __syncthreads();
   DED_STAMP(1)
   int buf = 0;
@@ -290,7 +526,7 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
     compute(w1, buf ^ 1);
   }
   DED_STAMP(2)
-  // second half -> LDS -> first half adds and stores
+  // second half -> LDS -> first half adds
   __syncthreads();
   float4* red = reinterpret_cast<float4*>(lds) + wn * ACC_U4 + lane;
   if (half == 1) {
@@ -311,9 +547,20 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
         float4 v = red[(t * 4 + rb) * 64];
         acc[t][rb] += f32x4_t{v.x, v.y, v.z, v.w};
       }
-    if (ng_raw < NG) store_tile(part + (int64_t)split * part_stride, out_row_stride, ng, N, rb0, lane, acc);
   }
   DED_STAMP(3)
+  const bool store_ok = ng_raw < NG;
+  if (splits == 1) {
+    if (half == 0 && store_ok) run_epilogue<EPI, 4>(epi, ng, N, rb0, rb0, row_scale, lane, acc);
+  } else if (finish_split(part, part_stride, split, splits, counters, NG, ng, rb0, lane, half == 0 && store_ok, acc,
+                          &s_flag) &&
+             store_ok) {
+    // both halves take part: wavefront (half, wn) finishes row blocks 2 * half, 2 * half + 1 of feature group wn
+    load_slices<2>(part, part_stride, splits, NG, ng, rb0, half * 2, lane, acc);
+    DED_STAMP(6)
+    run_epilogue<EPI, 2>(epi, ng, N, rb0, rb0 + half * 2, row_scale, lane, acc);
+  }
+  DED_STAMP(7)
 }
 
 // Debug knob: DED_GEMM_TUNE="nwn,splits" forces the kernel shape (nwn 0 = stream kernel).
@@ -333,12 +580,32 @@ struct Tune {
 constexpr int kCUs = 256;
 
 // relative cost of a shape: weight stream slowed down by activation reloads and uneven CU filling,
-// plus the split-K slices that are written here and read back by the consumer
+// plus the split-K slices that are written and read back inside the kernel
 double shape_cost(int64_t w_bytes, int64_t slice_bytes, int wgs, double x_per_w, int splits) {
   int rounds = (wgs + kCUs - 1) / kCUs;
   double eff = (double)wgs / (double)(rounds * kCUs);
   double stream = (double)w_bytes * (1.0 + 0.35 * x_per_w) / eff;
   return stream + 2.0 * (double)slice_bytes * (splits > 1 ? splits : 0);
+}
+
+template <int PLANES, int EPI>
+bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float* part, int64_t part_stride,
+                  const uint4* xp, const uint4* wp, int RB, int N, int KT, int* counters, const GemmEpilogue& epi,
+                  int nw, hipStream_t s) {
+  const int splits = plan.splits;
+#define DED_ARGS part, part_stride, xp, wp, RB, N, KT, splits, counters, epi
+  if (plan.nwn == 0) {
+    if (nw == 4) hipLaunchKernelGGL((gemm_stream_kernel<4, PLANES, EPI>), grid_stream, dim3(256), 0, s, DED_ARGS);
+    else if (nw == 2) hipLaunchKernelGGL((gemm_stream_kernel<2, PLANES, EPI>), grid_stream, dim3(128), 0, s, DED_ARGS);
+    else hipLaunchKernelGGL((gemm_stream_kernel<1, PLANES, EPI>), grid_stream, dim3(64), 0, s, DED_ARGS);
+    return true;
+  }
+  if (plan.nwn == 4) hipLaunchKernelGGL((gemm_wide_kernel<4, PLANES, EPI>), grid_wide, dim3(512), 0, s, DED_ARGS);
+  else if (plan.nwn == 3) hipLaunchKernelGGL((gemm_wide_kernel<3, PLANES, EPI>), grid_wide, dim3(384), 0, s, DED_ARGS);
+  else if (plan.nwn == 2) hipLaunchKernelGGL((gemm_wide_kernel<2, PLANES, EPI>), grid_wide, dim3(256), 0, s, DED_ARGS);
+  else return false;
+#undef DED_ARGS
+  return true;
 }
 
 }  // namespace
@@ -347,7 +614,7 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
   static const Tune tune;
   const int NG = (N + 16 * TN - 1) / (16 * TN), groups = K / (32 * PD), rg = rows_pad / 64;
   const int64_t w_bytes = (int64_t)NG * 64 * K * 2, slice = (int64_t)rows_pad * N * 4;
-  GemmPlan best{0, 4, 1};
+  GemmPlan best{0, 1, 1};
   double best_cost = 1e300;
   for (int nwn = 0; nwn <= 4; ++nwn) {
     if (tune.nwn >= 0 && nwn != tune.nwn) continue;
@@ -365,7 +632,7 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
       } else {
         if (groups / s < 2) continue;  // each half needs at least two chunks
         wgs = ((NG + nwn - 1) / nwn) * s * rg;
-        x_per_w = (double)planes / nwn;
+        x_per_w = (double)planes / nwn + 0.7;  // + barriers and LDS traffic of the wide kernel (calibrated)
       }
       double c = shape_cost(w_bytes, slice, wgs, x_per_w, s);
       if (c < best_cost) {
@@ -377,51 +644,45 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
   return best;
 }
 
+int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan) {
+  const int NG = (N + 16 * TN - 1) / (16 * TN);
+  const int gx = plan.nwn == 0 ? NG : (NG + plan.nwn - 1) / plan.nwn;
+  return gx * (rows_pad / 64);
+}
+
 bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed, int rows_pad,
-               int N, int K, int planes, const GemmPlan& plan, int64_t out_row_stride, hipStream_t s) {
+               int N, int K, int planes, const GemmPlan& plan, int* counters, const GemmEpilogue& epi,
+               hipStream_t s) {
   if (rows_pad <= 0 || rows_pad % 64 || N % 16 || K % (32 * PD) || (planes != 1 && planes != 2)) return false;
   const int RB = rows_pad / 16, KT = K / 32, groups = KT / PD;
   const int NG = (N + 16 * TN - 1) / (16 * TN);
   const int splits = plan.splits;
-  if (splits < 1 || splits > groups) return false;
+  if (splits < 1 || splits > groups || !counters) return false;
+  if (plan.nwn != 0 && groups / splits < 2) return false;
+  if (splits > 1 && part_stride < (int64_t)rows_pad * NG * 16 * TN) return false;
+  if ((epi.kind == EPI_RESIDUAL || epi.kind == EPI_QKV || epi.kind == EPI_SILU) && N % 64) return false;
+  int nw = plan.nw >= 4 ? 4 : plan.nw >= 2 ? 2 : 1;
+  while (nw > 1 && splits * nw > groups) nw /= 2;  // every wavefront needs at least one k group
   const uint4* xp = reinterpret_cast<const uint4*>(x_packed);
   const uint4* wp = reinterpret_cast<const uint4*>(w_packed);
-#define DED_LAUNCH_T(KERNEL, A, B, GX, THREADS)                                                            \
-  hipLaunchKernelGGL((KERNEL<A, B>), dim3(GX, splits, RB / 4), dim3(THREADS), 0, s, part, part_stride, xp, \
-                     wp, RB, N, KT, splits, out_row_stride)
-#define DED_LAUNCH(KERNEL, A, B, GX) DED_LAUNCH_T(KERNEL, A, B, GX, A * 64)
-#define DED_LAUNCH_W(A, B, GX) DED_LAUNCH_T(gemm_wide_kernel, A, B, GX, A * 128)
-  if (plan.nwn == 0) {
-    int nw = plan.nw >= 4 ? 4 : plan.nw >= 2 ? 2 : 1;
-    while (nw > 1 && splits * nw > groups) nw /= 2;  // every wavefront needs at least one k group
-    if (planes == 2) {
-      if (nw == 4) DED_LAUNCH(gemm_stream_kernel, 4, 2, NG);
-      else if (nw == 2) DED_LAUNCH(gemm_stream_kernel, 2, 2, NG);
-      else DED_LAUNCH(gemm_stream_kernel, 1, 2, NG);
-    } else {
-      if (nw == 4) DED_LAUNCH(gemm_stream_kernel, 4, 1, NG);
-      else if (nw == 2) DED_LAUNCH(gemm_stream_kernel, 2, 1, NG);
-      else DED_LAUNCH(gemm_stream_kernel, 1, 1, NG);
-    }
-    return true;
+  dim3 gs(NG, splits, RB / 4), gw(plan.nwn ? (NG + plan.nwn - 1) / plan.nwn : 1, splits, RB / 4);
+#define DED_GO(P, E) return launch_shape<P, E>(plan, gs, gw, part, part_stride, xp, wp, RB, N, KT, counters, epi, nw, s)
+  switch (epi.kind) {
+    case EPI_LOGITS:
+      if (planes == 2) DED_GO(2, EPI_LOGITS);
+      return false;
+    case EPI_QKV:
+      if (planes == 2) DED_GO(2, EPI_QKV);
+      return false;
+    case EPI_SILU:
+      if (planes == 2) DED_GO(2, EPI_SILU);
+      return false;
+    case EPI_RESIDUAL:
+      if (planes == 1) DED_GO(1, EPI_RESIDUAL);
+      return false;
   }
-  if (groups / splits < 2) return false;
-  const int gx = (NG + plan.nwn - 1) / plan.nwn;
-  if (planes == 2) {
-    if (plan.nwn == 4) DED_LAUNCH_W(4, 2, gx);
-    else if (plan.nwn == 3) DED_LAUNCH_W(3, 2, gx);
-    else if (plan.nwn == 2) DED_LAUNCH_W(2, 2, gx);
-    else return false;
-  } else {
-    if (plan.nwn == 4) DED_LAUNCH_W(4, 1, gx);
-    else if (plan.nwn == 3) DED_LAUNCH_W(3, 1, gx);
-    else if (plan.nwn == 2) DED_LAUNCH_W(2, 1, gx);
-    else return false;
-  }
-#undef DED_LAUNCH
-#undef DED_LAUNCH_W
-#undef DED_LAUNCH_T
-  return true;
+#undef DED_GO
+  return false;
 }
 
 }  // namespace ded

@@ -1,6 +1,5 @@
-// 16-bit path, everything that is not a contraction: weight re-layout, embedding gather, residual add +
-// RMSNorm, the QKV epilogue (split-K sum, rotary embedding, cache append), SiLU*up, cache compaction
-// and the plain <-> fragment layout conversions.  Number formats: see bf16_layout.h.
+// 16-bit path, what is neither a contraction nor a GEMM epilogue: weight re-layout, embedding gather,
+// cache compaction and the plain <-> fragment layout conversions.  Number formats: see bf16_layout.h.
 #include <algorithm>
 
 #include "bf16_layout.h"
@@ -65,8 +64,21 @@ __device__ inline F8 sum_parts8(const float* part, int n_part, int64_t part_stri
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
+// Source feature of packed feature n (see PERM_* in ded_kernels.h).  F = half the row count for PERM_GATE_UP.
+__device__ inline int packw_source_row(int n, int perm, int F) {
+  if (perm == PERM_NONE) return n;
+  const int t = (n >> 4) & 3, e = n & 15;
+  if (perm == PERM_ROPE) {  // per 128-dim head: group j holds dims [32j, 32j+32) and their partners + 64
+    const int head = n >> 7, j = (n >> 6) & 1;
+    const int dim = 32 * j + 16 * (t & 1) + e + (t >= 2 ? 64 : 0);
+    return head * 128 + dim;
+  }
+  const int f = 32 * (n >> 6) + 16 * (t & 1) + e;  // PERM_GATE_UP: gate f in tiles 0,1, up f in tiles 2,3
+  return t >= 2 ? F + f : f;
+}
+
 // dst: PackW (f16) with the feature count padded to a multiple of 64 (padding features are zero)
-__global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K) {
+__global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __restrict__ src, int N, int K, int perm) {
   int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // destination 16-byte unit
   int64_t total = (int64_t)((N + 63) / 64 * 64) * K / 8;
   if (u >= total) return;
@@ -80,7 +92,8 @@ __global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __rest
   int k = kt * 32 + (lane >> 4) * 8;
   uint4 out = make_uint4(0, 0, 0, 0);
   if (n < N) {
-    uint4 in = *reinterpret_cast<const uint4*>(src + (int64_t)n * K + k);
+    int row = packw_source_row(n, perm, N / 2);
+    uint4 in = *reinterpret_cast<const uint4*>(src + (int64_t)row * K + k);
     uint32_t w[4] = {in.x, in.y, in.z, in.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[i] = pk(bf16_to_f16((uint16_t)(w[i] & 0xffffu)), bf16_to_f16((uint16_t)(w[i] >> 16)));
@@ -88,149 +101,52 @@ __global__ void pack_weight_kernel(uint4* __restrict__ dst, const bf16_t* __rest
   }
   dst[u] = out;
 }
-void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, hipStream_t s) {
+void bf16_pack_weight(bf16_t* dst, const bf16_t* src, int N, int K, int perm, hipStream_t s) {
   int64_t units = (int64_t)((N + 63) / 64 * 64) * K / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
-                     reinterpret_cast<uint4*>(dst), src, N, K);
+                     reinterpret_cast<uint4*>(dst), src, N, K, perm);
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ void bf16_embed_kernel(float* __restrict__ x, const bf16_t* __restrict__ emb,
-                                  const int32_t* __restrict__ token, int d) {
+// Embedding gather: x = emb[token] (fp32 residual stream), y = (x * gain) as hi/lo f16 in PackX for the first
+// GEMM, ssq[r][g] = sum of x^2 over the 64 features of group g (the consumer turns that into 1/rms).
+__global__ __launch_bounds__(256) void bf16_embed_kernel(float* __restrict__ x, uint4* __restrict__ y,
+                                                         float* __restrict__ ssq, const bf16_t* __restrict__ emb,
+                                                         const float* __restrict__ gain,
+                                                         const int32_t* __restrict__ token, int rows, int RB, int d) {
   int r = blockIdx.x;
-  const bf16_t* src = emb + (int64_t)token[r] * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) x[(int64_t)r * d + i] = bf16_to_f32(src[i]);
-}
-void bf16_embed(float* x, const bf16_t* emb, const StepMeta& m, int d, hipStream_t s) {
-  hipLaunchKernelGGL(bf16_embed_kernel, dim3(m.rows), dim3(256), 0, s, x, emb, m.token, d);
-}
-
-// ------------------------------------------------------------------------------------------
-// x[r] += sum of the pending split-K slices; y = x * rsqrt(mean(x^2) + eps) * gain as hi/lo f16 in PackX.
-__global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part,
-                                                          int n_part, int64_t part_stride, uint4* __restrict__ y,
-                                                          const float* __restrict__ gain, int RB, int d, float eps) {
-  __shared__ float sh[4];
-  int r = blockIdx.x;
-  float* xr = x + (int64_t)r * d;
-  float ss = 0.f;
-  for (int u = threadIdx.x; u < d / 8; u += 256) {
-    F8 v = load8(xr + u * 8);
-    if (n_part > 0) {
-      F8 p = sum_parts8(part, n_part, part_stride, (int64_t)r * d + u * 8);
+  const bool real = r < rows;  // padding rows (up to the 64-row granule of the GEMMs) are cleared
+  const bf16_t* src = emb + (int64_t)(real ? token[r] : 0) * d;
+  for (int u = threadIdx.x; u < d / 8; u += 256) {  // d % 64 == 0: whole wavefront iterations only
+    uint4 in = real ? *reinterpret_cast<const uint4*>(src + u * 8) : make_uint4(0, 0, 0, 0);
+    uint32_t w[4] = {in.x, in.y, in.z, in.w};
+    F8 v;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v.v[i] += p.v[i];
-      store8(xr + u * 8, v);
+    for (int i = 0; i < 4; ++i) {
+      v.v[2 * i] = bf16_to_f32((uint16_t)(w[i] & 0xffffu));
+      v.v[2 * i + 1] = bf16_to_f32((uint16_t)(w[i] >> 16));
     }
+    store8(x + (int64_t)r * d + u * 8, v);
+    float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) ss += v.v[i] * v.v[i];
-  }
-  ss = block_sum_256(ss, sh);  // the barriers inside also order the x stores before the reads below
-  float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int u = threadIdx.x; u < d / 8; u += 256) {
-    F8 v = load8(xr + u * 8);
+    ss += __shfl_xor(ss, 1);  // 8 consecutive lanes = one 64-feature group
+    ss += __shfl_xor(ss, 2);
+    ss += __shfl_xor(ss, 4);
+    if ((threadIdx.x & 7) == 0) ssq[(int64_t)r * (d / 64) + (u >> 3)] = ss;
     F8 g = load8(gain + u * 8);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v.v[i] = v.v[i] * inv * g.v[i];
+    for (int i = 0; i < 8; ++i) v.v[i] *= g.v[i];
     uint4 hi, lo;
     to_f16x8_split(v, hi, lo);
     y[packx_index(r, u * 8, RB, 0) >> 3] = hi;
     y[packx_index(r, u * 8, RB, 1) >> 3] = lo;
   }
 }
-void bf16_add_rmsnorm(float* x, const float* part, int n_part, int64_t part_stride, bf16_t* y_packed,
-                      const float* gain, int rows, int rows_pad, int d, float eps, hipStream_t s) {
-  if (rows <= 0) return;
-  hipLaunchKernelGGL(add_rmsnorm_kernel, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
-                     reinterpret_cast<uint4*>(y_packed), gain, rows_pad / 16, d, eps);
-}
-
-// ------------------------------------------------------------------------------------------
-// QKV epilogue.  One thread owns 8 head dims i0..i0+7 of the first half of a head and their rotary
-// partners i0+64..i0+71.  Query heads go to PackQ (hi/lo), key heads (rotated) and value heads of real
-// nodes go to the cache fragments (f16) at slot prefix_len + node.
-__global__ __launch_bounds__(256) void qkv_epilogue_kernel(
-    const float* __restrict__ part, int n_part, int64_t part_stride, bf16_t* __restrict__ qp,
-    bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, const float2* __restrict__ tab,
-    const int32_t* __restrict__ seq_p, const int32_t* __restrict__ seq_n, int n_step, int H, int Hkv, int cap) {
-  const int hd = 128, half = 64;
-  int r = blockIdx.x;
-  int b = r / n_step, node = r - b * n_step;
-  int G = H / Hkv;
-  int width = (H + 2 * Hkv) * hd;
-  bool real = node < seq_n[b];
-  int slot = seq_p[b] + node;
-  int units = (H + 2 * Hkv) * 8;
-  for (int u = blockIdx.y * 256 + threadIdx.x; u < units; u += gridDim.y * 256) {
-    int hs = u >> 3, i0 = (u & 7) * 8;
-    if (hs >= H && !real) continue;
-    int64_t off = (int64_t)r * width + (int64_t)hs * hd + i0;
-    F8 a = sum_parts8(part, n_part, part_stride, off);
-    F8 c = sum_parts8(part, n_part, part_stride, off + half);
-    if (hs < H + Hkv) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float2 cs = tab[(int64_t)r * half + i0 + i];
-        float ra = a.v[i] * cs.x - c.v[i] * cs.y;
-        float rc = c.v[i] * cs.x + a.v[i] * cs.y;
-        a.v[i] = ra;
-        c.v[i] = rc;
-      }
-    }
-    if (hs < H) {
-      int kvh = hs / G, g = hs - kvh * G;
-      int vr = g * n_step + node;
-      bf16_t* base = qp + ((int64_t)b * Hkv + kvh) * ((int64_t)G * n_step * hd * 2);
-      uint4 hi, lo;
-      to_f16x8_split(a, hi, lo);
-      *reinterpret_cast<uint4*>(base + packq_index(vr, i0, 0)) = hi;
-      *reinterpret_cast<uint4*>(base + packq_index(vr, i0, 1)) = lo;
-      to_f16x8_split(c, hi, lo);
-      *reinterpret_cast<uint4*>(base + packq_index(vr, i0 + half, 0)) = hi;
-      *reinterpret_cast<uint4*>(base + packq_index(vr, i0 + half, 1)) = lo;
-    } else if (hs < H + Hkv) {
-      bf16_t* base = kc + ((int64_t)b * Hkv + (hs - H)) * ((int64_t)cap * hd);
-      *reinterpret_cast<uint4*>(base + packk_index(slot, i0)) = to_f16x8(a);
-      *reinterpret_cast<uint4*>(base + packk_index(slot, i0 + half)) = to_f16x8(c);
-    } else {
-      bf16_t* base = vc + ((int64_t)b * Hkv + (hs - H - Hkv)) * ((int64_t)cap * hd);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        base[packvt_index(slot, i0 + i)] = f32_to_f16(a.v[i]);
-        base[packvt_index(slot, i0 + half + i)] = f32_to_f16(c.v[i]);
-      }
-    }
-  }
-}
-void bf16_qkv_epilogue(const float* part, int n_part, int64_t part_stride, bf16_t* q_packed, bf16_t* kc,
-                       bf16_t* vc, const float2* tab, const StepMeta& m, const ModelDims& md, hipStream_t s) {
-  int units = (md.H + 2 * md.Hkv) * 8;
-  int gy = std::min(8, (units + 255) / 256);
-  hipLaunchKernelGGL(qkv_epilogue_kernel, dim3(m.rows, gy), dim3(256), 0, s, part, n_part, part_stride, q_packed,
-                     kc, vc, tab, m.seq_p, m.seq_n, m.n_step, md.H, md.Hkv, md.cap);
-}
-
-// ------------------------------------------------------------------------------------------
-__global__ void silu_mul_kernel(uint4* __restrict__ h, const float* __restrict__ part, int n_part,
-                                int64_t part_stride, int RB, int F) {
-  int r = blockIdx.y;
-  int u = blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= F / 8) return;
-  int64_t off = (int64_t)r * 2 * F + u * 8;
-  F8 g = sum_parts8(part, n_part, part_stride, off);
-  F8 up = sum_parts8(part, n_part, part_stride, off + F);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) g.v[i] = g.v[i] / (1.0f + __expf(-g.v[i])) * up.v[i];
-  uint4 hi, lo;
-  to_f16x8_split(g, hi, lo);
-  h[packx_index(r, u * 8, RB, 0) >> 3] = hi;
-  h[packx_index(r, u * 8, RB, 1) >> 3] = lo;
-}
-void bf16_silu_mul(bf16_t* h_packed, const float* part, int n_part, int64_t part_stride, int rows, int rows_pad,
-                   int F, hipStream_t s) {
-  if (rows <= 0 || F <= 0) return;
-  hipLaunchKernelGGL(silu_mul_kernel, dim3((F / 8 + 255) / 256, rows), dim3(256), 0, s,
-                     reinterpret_cast<uint4*>(h_packed), part, n_part, part_stride, rows_pad / 16, F);
+void bf16_embed(float* x, bf16_t* y_packed, float* ssq, const bf16_t* emb, const float* gain, const StepMeta& m,
+                int rows_pad, int d, hipStream_t s) {
+  hipLaunchKernelGGL(bf16_embed_kernel, dim3(rows_pad), dim3(256), 0, s, x, reinterpret_cast<uint4*>(y_packed), ssq, emb,
+                     gain, m.token, m.rows, rows_pad / 16, d);
 }
 
 // ------------------------------------------------------------------------------------------
