@@ -24,9 +24,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
-# HBM bytes measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/*_pmc.md); None = not measured yet
-GEMM_TRAFFIC_BYTES_PER_STEP = None
-ATTN_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM traffic per launch, KiB, as read by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --pmc-mode`
+# (summary and commands: profiles/c3_verify_step_hbm_traffic_pmc.md).  A plain 1 GiB device copy in the same
+# run reads 0.5 GiB on FETCH_SIZE (wide coalesced loads are counted at half their size) and 1.0 GiB on
+# WRITE_SIZE, hence the factors.
+PMC_FETCH_FACTOR = 2.0
+PMC_WRITE_FACTOR = 1.0
+PMC_KIB = {  # class: (FETCH_SIZE, WRITE_SIZE) mean per launch
+    "gemm_qkv": (59724.1, 14346.0),
+    "gemm_o": (21085.6, 6282.0),
+    "gemm_gate_up": (97837.9, 12394.8),
+    "gemm_down": (52189.9, 6282.0),
+    "gemm_lm_head": (140278.0, 24012.2),
+    "tree_attention_c2": (37511.8, 16640.1),
+}
+
+
+def pmc_bytes(cls):
+    f, w = PMC_KIB[cls]
+    return (f * PMC_FETCH_FACTOR + w * PMC_WRITE_FACTOR) * 1024.0
 
 
 def log(*a):
@@ -127,7 +143,7 @@ def attention_only_bench(di, iters=40):
     us = ms / n * 1e3
     return {"bound": "hbm", "kernel": "tree_attn_partial_kernel", "workload": "c2 attention-only",
             "achieved": alg / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": ATTN_TRAFFIC_BYTES_PER_LAUNCH,
+            "frac": alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": pmc_bytes("tree_attention_c2"),
             "us_per_launch": us, "merge_us_per_launch": ms_merge / n * 1e3, "algorithmic_bytes": alg}
 
 
@@ -243,6 +259,14 @@ def main():
     gemm_gbs = w_bytes / (gemm_ms * 1e-3) / 1e9
     gemm_tflops = 2.0 * wl.n_nodes * gemm_weight_elems(cfg) / (gemm_ms * 1e-3) / 1e12
     kernels_ms = {k: round(v[0] / prof_steps, 4) for k, v in prof.items() if v[1]}
+    # dominant kernel: the gate/up projection (largest share of the step); one launch streams 2F x d bf16 weights
+    gu_us = prof["gemm_gate_up"][0] / max(prof["gemm_gate_up"][1], 1) * 1e3 if cfg.n_layers else float("nan")
+    gu_bytes = 2.0 * 2 * cfg.d_ffn * cfg.d_model
+    gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9
+    full_model = cfg.n_layers == wl.model.n_layers
+    per_launch = {c: prof[c][0] / max(prof[c][1], 1) * 1e3 for c in gemm_classes}
+    gemm_traffic_step = (sum(pmc_bytes(c) for c in gemm_classes[:4]) * cfg.n_layers + pmc_bytes("gemm_lm_head")
+                         if full_model else None)
 
     out = {
         "metric": "tree-verify steps/s at 7B shape (64-node tree, 1024-token prefix, batch 1)",
@@ -267,12 +291,20 @@ def main():
         "raw_trigram_tree": {"steps_per_s": raw_steps / dt_raw, "verified_tokens_per_s": n_tok_raw / dt_raw,
                              "mean_accepted_per_step": n_tok_raw / raw_steps},
         "kernel_ms_per_step": kernels_ms,
-        "roofline": {"bound": "hbm", "kernel": "gemm_wide_kernel + gemm_stream_kernel (all projection GEMMs of a step)",
-                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_STEP, "launches_per_step": int(gemm_launches),
-                     "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
-                     "algorithmic_bytes_per_step": w_bytes, "mfma_tflops": gemm_tflops,
-                     "mfma_frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
+        "roofline": {"bound": "hbm",
+                     "kernel": "gate/up projection GEMM with SiLU*up epilogue (gemm_wide_kernel, 3 feature groups per "
+                               "workgroup, 2 activation planes, split-K 2): 22016 x 4096 bf16 weights per launch",
+                     "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
+                     "traffic": pmc_bytes("gemm_gate_up") if full_model else None,
+                     "avg_launch_us": gu_us, "algorithmic_bytes_per_launch": gu_bytes,
+                     "launches_per_step": cfg.n_layers, "share_of_step": gu_us * 1e-3 * cfg.n_layers / (dt / args.steps * 1e3)},
+        "roofline_all_gemms": {"bound": "hbm", "kernel": "all projection GEMMs of a step (QKV, O, gate/up, down, LM head)",
+                               "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
+                               "traffic_per_step": gemm_traffic_step, "launches_per_step": int(gemm_launches),
+                               "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
+                               "us_per_launch_by_class": {k: round(v, 2) for k, v in per_launch.items()},
+                               "algorithmic_bytes_per_step": w_bytes, "mfma_tflops": gemm_tflops,
+                               "mfma_frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
     }
     if not args.no_attn:
         out["roofline_tree_attention"] = attention_only_bench(di)
