@@ -47,10 +47,13 @@ enum { DED_F32 = 0, DED_BF16 = 1 };
 
 typedef struct ded_ctx ded_ctx; /* opaque */
 
-/* Model and capacity description.  dtype is the storage type of the weight matrices, of the KV
- * cache and of the GEMM inputs (accumulation, residual stream, norms and soft-max statistics are
- * always fp32).  DED_BF16 needs head_dim == 128, d_model % 128 == 0, d_ffn % 128 == 0,
- * vocab % 16 == 0 and kv_capacity % 64 == 0; max_nodes <= 256. */
+/* Model and capacity description.  dtype is the type of the weight matrices, K/V rows and q / o
+ * tensors that cross this interface (accumulation, residual stream, norms and soft-max statistics
+ * are always fp32).  With DED_BF16 the library keeps 2-byte storage but computes with IEEE half
+ * matrix-core operands: bf16 weights are widened exactly, K/V produced by the model are kept as
+ * half, GEMM inputs and queries as hi + lo half pairs.  DED_BF16 needs head_dim == 128,
+ * d_model % 128 == 0, d_ffn % 128 == 0, vocab % 16 == 0 and kv_capacity % 64 == 0;
+ * max_nodes <= 256. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rope_base; /* rotary base; pairing is (i, i + head_dim/2), angle pos * base^(-2i/head_dim) */
