@@ -120,18 +120,46 @@ __device__ inline void split4_f16(const float (&v)[4], uint2& hi, uint2& lo) {
 // time (packw_source_row) so that tiles t and t + 2 of a group hold partner features: rotary pairs
 // (i, i + 64), or gate / up.
 // ------------------------------------------------------------------------------------------
-// RMSNorm scale of row rb0 * 16 + lane of the GEMM input (the producer stored sum(x^2) per 64-feature group).
-// Fetched right after the first weight loads are issued, as one batch of independent loads, so that neither
-// the main loop nor the epilogue waits for it.
-__device__ inline float input_row_scale(const GemmEpilogue& e, int rb0, int lane) {
-  if (!e.ssq_in) return 1.f;
-  const float2* p = reinterpret_cast<const float2*>(e.ssq_in + (int64_t)(rb0 * 16 + lane) * e.ssq_groups);
+// RMSNorm scale of the GEMM input rows: 1 / sqrt(sum(x^2) / d + eps), from the per-(row, 64-feature group)
+// sums that the producer stored.  The sums were written by another kernel, usually from another XCD, and a
+// load issued when they are needed costs ~3 us; at kernel start it would delay the first weight chunk (loads
+// return in order).  So the wavefronts of a workgroup share the job: each fetches a slice of the groups for
+// row rb0 * 16 + lane a few iterations before its k loop ends (ssq_issue; <= 8 float2 registers), adds them
+// up after the loop, and the partial sums meet in LDS at the barrier the kernel has there anyway.
+constexpr int SSQ_REGS = 8;
+struct SsqPart {
+  float2 v[SSQ_REGS];
+};
+__device__ inline void ssq_clear(SsqPart& p) {
+#pragma unroll
+  for (int i = 0; i < SSQ_REGS; ++i) p.v[i] = make_float2(0.f, 0.f);
+}
+// wavefront `wv` of `nwv` takes float2 units [wv * per, wv * per + per) of the row's ssq_groups / 2
+__device__ inline void ssq_issue(const GemmEpilogue& e, int rb0, int lane, int wv, int nwv, SsqPart& p) {
+  if (!e.ssq_in) return;
+  const int n2 = e.ssq_groups >> 1, per = (n2 + nwv - 1) / nwv, g0 = wv * per;
+  const float2* src = reinterpret_cast<const float2*>(e.ssq_in + (int64_t)(rb0 * 16 + lane) * e.ssq_groups);
+#pragma unroll
+  for (int i = 0; i < SSQ_REGS; ++i)
+    if (i < per && g0 + i < n2) p.v[i] = src[g0 + i];
+}
+// partial sum of this wavefront's slice -> LDS (call before a workgroup barrier)
+__device__ inline void ssq_publish(const GemmEpilogue& e, int rb0, int lane, int wv, int nwv, const SsqPart& p,
+                                   float* s_ssq) {
+  if (!e.ssq_in) return;
   float s = 0.f;
-#pragma unroll 32
-  for (int g = 0; g < e.ssq_groups / 2; ++g) {
-    float2 v = p[g];
-    s += v.x + v.y;
-  }
+#pragma unroll
+  for (int i = 0; i < SSQ_REGS; ++i) s += p.v[i].x + p.v[i].y;
+  const int n2 = e.ssq_groups >> 1, per = (n2 + nwv - 1) / nwv, g0 = wv * per;
+  const float2* src = reinterpret_cast<const float2*>(e.ssq_in + (int64_t)(rb0 * 16 + lane) * e.ssq_groups);
+  for (int i = SSQ_REGS; i < per && g0 + i < n2; ++i) s += src[g0 + i].x + src[g0 + i].y;  // very wide rows only
+  s_ssq[wv * 64 + lane] = s;
+}
+// after that barrier: scale of row rb0 * 16 + lane (partials added in wavefront order)
+__device__ inline float ssq_scale(const GemmEpilogue& e, int lane, int nwv, const float* s_ssq) {
+  if (!e.ssq_in) return 1.f;
+  float s = 0.f;
+  for (int w = 0; w < nwv; ++w) s += s_ssq[w * 64 + lane];
   return 1.0f / sqrtf(s * e.inv_k + e.eps);
 }
 
@@ -287,6 +315,7 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
                                                                  int splits, int* __restrict__ counters,
                                                                  GemmEpilogue epi) {
   __shared__ float4 red[(NW > 1 ? NW / 2 : 1) * TN * 4 * 64];
+  __shared__ float s_ssq[NW * 64];
   __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ng = blockIdx.x;
@@ -306,7 +335,8 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
     for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   DED_STAMP(0)
-  float row_scale = 1.f;
+  SsqPart ssq;
+  ssq_clear(ssq);
   if (g_begin < g_end) {
     const uint4* wsrc = wp + (((int64_t)ng * KT * TN) << 6) + lane;
     // per k step the activations of the 4 row blocks x 2 planes (hi, lo) are 8 KiB of contiguous memory
@@ -339,19 +369,23 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
     const int kt_last = g_end * PD - RING;  // first step of the last ring-full (range length % RING == 0)
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j, kt + j);
-    row_scale = input_row_scale(epi, rb0, lane);
+    const int kt_ssq = kt_last - 8 * RING > kt ? kt_last - 8 * RING : kt;  // 8 ring turns before the end
+    if (kt >= kt_last) ssq_issue(epi, rb0, lane, wave, NW, ssq);
     for (; kt < kt_last; kt += RING) {
 #pragma unroll
       for (int j = 0; j < RING; ++j) {
         compute(j);
         issue(j, kt + RING + j);
       }
+      if (kt == kt_ssq) ssq_issue(epi, rb0, lane, wave, NW, ssq);
     }
 #pragma unroll
     for (int j = 0; j < RING; ++j) compute(j);
   } else {
-    row_scale = input_row_scale(epi, rb0, lane);
+    ssq_issue(epi, rb0, lane, wave, NW, ssq);
   }
+  ssq_publish(epi, rb0, lane, wave, NW, ssq, s_ssq);
+  if (NW == 1) __syncthreads();
 
   DED_STAMP(2)
   // combine the NW k ranges: wave w += wave w + stride, stride = NW/2 .. 1
@@ -383,6 +417,7 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
     }
   }
   DED_STAMP(3)
+  const float row_scale = ssq_scale(epi, lane, NW, s_ssq);  // the reduction above had at least one barrier
   if (splits == 1) {
     if (wave == 0) run_epilogue<EPI, 4>(epi, ng, N, rb0, rb0, row_scale, lane, acc);
   } else if (finish_split(part, part_stride, split, splits, counters, gridDim.x, ng, rb0, lane, wave == 0, acc, &s_flag)) {
@@ -416,6 +451,7 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   constexpr int ACC_U4 = TN * 4 * 64;             // float4 units of one wavefront's accumulators
   constexpr int LDS_U4 = (2 * 2 * CHUNK_U4 > NWN * ACC_U4) ? 2 * 2 * CHUNK_U4 : NWN * ACC_U4;
   __shared__ uint4 lds[LDS_U4];                   // [half][buffer][chunk]; reused for the final reduction
+  __shared__ float s_ssq[2 * NWN * 64];
   __shared__ int s_flag;
   const int half = threadIdx.x / TH;
   const int tid = threadIdx.x - half * TH, lane = tid & 63, wn = tid >> 6;
@@ -496,37 +532,82 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   };
 
   DED_STAMP(0)
-  // Weight chunks are fetched two chunks ahead (three register buffers, rotated), activation chunks one
-  // ahead (LDS double buffer).  In every iteration the activation loads are issued BEFORE the weight loads
-  // of the farther chunk, so that waiting for them (loads retire in order) leaves the weight loads in flight.
-  // Both halves run the same number of iterations, hence the same number of barriers (n_chunks >= 2).
-  // (Fetching three chunks ahead, or four k steps in the stream kernel, measured no faster.)
+  // Software pipeline.  Loads return in order, so waiting for an activation chunk also waits for every
+  // weight chunk issued before it: with activations one chunk ahead an iteration could not be shorter than
+  // one HBM round trip (measured: 16 iterations of 1.4 us).  Hence activations are fetched TWO chunks ahead
+  // (registers; the LDS copy stays double buffered) and weights THREE: the wait for activation chunk c + 1
+  // then only needs loads that are two iterations old.  In every iteration the activation loads are issued
+  // before the weight loads.  Both halves run the same number of iterations and barriers (n_chunks >= 2).
+  // Kernel shapes whose chunks hold two k steps keep the shallower pipeline (activations one chunk ahead,
+  // weights two): their iterations are twice as long, and the deeper one does not fit the register file.
+  constexpr bool DEEP = CH == 1;
+  SsqPart ssq;
+  ssq_clear(ssq);
+  const int wv = threadIdx.x >> 6;
+  const int c_ssq = n_chunks - 14;  // fetch the row sums ~10 iterations before the loop ends
   WChunk w0 = load_w(0);
   XStage x0 = load_x(0);
   WChunk w1 = load_w(1);
-  const float row_scale = input_row_scale(epi, rb0, lane);
-  store_x(0, x0);
-  __syncthreads();
-  DED_STAMP(1)
   int buf = 0;
-  for (int c = 0; c + 2 < n_chunks; ++c) {
-    XStage xn = load_x(c + 1);
-    WChunk w2 = load_w(c + 2);
-    compute(w0, buf);
-    store_x(buf ^ 1, xn);
+  if constexpr (DEEP) {
+    XStage x1 = load_x(1);
+    WChunk w2 = w1;
+    if (n_chunks > 2) w2 = load_w(2);
+    store_x(0, x0);
     __syncthreads();
-    w0 = w1;
-    w1 = w2;
-    buf ^= 1;
-  }
-  {  // last two chunks: nothing left to prefetch
-    XStage xn = load_x(n_chunks - 1);
+    DED_STAMP(1)
+    if (c_ssq < 0) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
+    for (int c = 0; c + 3 < n_chunks; ++c) {
+      XStage x2 = load_x(c + 2);
+      WChunk w3 = load_w(c + 3);
+      if (c == c_ssq) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
+      compute(w0, buf);
+      store_x(buf ^ 1, x1);
+      __syncthreads();
+      w0 = w1;
+      w1 = w2;
+      w2 = w3;
+      x1 = x2;
+      buf ^= 1;
+    }
+    if (n_chunks > 2) {  // third-last chunk: one more activation chunk to fetch, no weights
+      XStage x2 = load_x(n_chunks - 1);
+      compute(w0, buf);
+      store_x(buf ^ 1, x1);
+      __syncthreads();
+      w0 = w1;
+      w1 = w2;
+      x1 = x2;
+      buf ^= 1;
+    }
+    compute(w0, buf);  // second-last
+    store_x(buf ^ 1, x1);
+    __syncthreads();
+    compute(w1, buf ^ 1);  // last
+  } else {
+    store_x(0, x0);
+    __syncthreads();
+    DED_STAMP(1)
+    if (c_ssq < 0) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
+    for (int c = 0; c + 2 < n_chunks; ++c) {
+      XStage xn = load_x(c + 1);
+      WChunk w2 = load_w(c + 2);
+      if (c == c_ssq) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
+      compute(w0, buf);
+      store_x(buf ^ 1, xn);
+      __syncthreads();
+      w0 = w1;
+      w1 = w2;
+      buf ^= 1;
+    }
+    XStage xn = load_x(n_chunks - 1);  // last two chunks: nothing left to prefetch
     compute(w0, buf);
     store_x(buf ^ 1, xn);
     __syncthreads();
     compute(w1, buf ^ 1);
   }
   DED_STAMP(2)
+  ssq_publish(epi, rb0, lane, threadIdx.x >> 6, 2 * NWN, ssq, s_ssq);
   // second half -> LDS -> first half adds
   __syncthreads();
   float4* red = reinterpret_cast<float4*>(lds) + wn * ACC_U4 + lane;
@@ -550,6 +631,7 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
       }
   }
   DED_STAMP(3)
+  const float row_scale = ssq_scale(epi, lane, 2 * NWN, s_ssq);
   const bool store_ok = ng_raw < NG;
   if (splits == 1) {
     if (half == 0 && store_ok) run_epilogue<EPI, 4>(epi, ng, N, rb0, rb0, row_scale, lane, acc);
