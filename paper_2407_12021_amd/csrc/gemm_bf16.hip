@@ -54,7 +54,8 @@ typedef f32x4_t Acc[TN][4];  // one wavefront's tile: 4 feature tiles x 4 row bl
 
 // Split-K slices travel between workgroups of one launch, which may sit on different XCDs with separate
 // L2 caches.  Instead of device-scope fences (a whole-L2 write-back and invalidate per workgroup, measured
-// at 3-4x the kernel time) the slices are written and read with device-scope relaxed atomic accesses, which
+// at 3-4x the kernel time; even an acquire fence in the last workgroup alone, followed by plain 16-byte
+// loads, was 10-20 % slower) the slices are written and read with device-scope relaxed atomic accesses, which
 // go through to the memory side on their own; ordering comes from waiting for the stores to complete
 // before the ticket is taken, and from the ticket's return value before the loads are issued.
 // A slice is private to the kernel, so it is kept in accumulator order: tile (row group, feature group) ->
