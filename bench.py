@@ -147,6 +147,54 @@ def attention_only_bench(di, iters=40):
             "us_per_launch": us, "merge_us_per_launch": ms_merge / n * 1e3, "algorithmic_bytes": alg}
 
 
+def large_rows_bench(di, steps=8):
+    """The projection GEMMs where they are matrix-core bound: batched trees give hundreds of rows per weight.
+    7B-shape layers (2 of them), batch 8 x 256-node trees = 2048 rows, and the 13B shape with batch 4 x 128 =
+    512 rows; empty prefixes (the attention share does not matter here).  Times are HIP-event brackets per
+    kernel class.  'executed' counts the hi and lo activation planes (two matrix instructions per useful one in
+    the QKV / gate-up / LM-head GEMMs), 'useful' counts 2 * rows * N * K once."""
+    import numpy as np
+    from paper_2407_12021_amd import Verifier
+    out = []
+    for label, base, batch, nodes in (("7B shape, 8 x 256-node trees", di.WORKLOADS["c3"].model, 8, 256),
+                                      ("13B shape, 4 x 128-node trees", di.WORKLOADS["c4"].model, 4, 128)):
+        cfg = base.with_layers(2)
+        w = di.make_weights(cfg, seed=0, threads=16)
+        ver = Verifier(cfg, w, max_batch=batch, kv_capacity=nodes + 64, max_nodes=nodes)
+        del w
+        parent = di.random_tree(nodes, None, seed=3)
+        g = np.random.default_rng(5)
+        toks = [g.integers(0, cfg.vocab, size=nodes) for _ in range(batch)]
+        run = lambda: (ver.verify_step([0] * batch, [parent] * batch, toks), ver.accept(mode=0))
+        for _ in range(2):
+            run()
+        ver.profile(True)
+        for _ in range(steps):
+            run()
+        prof = ver.profile_read()
+        ver.profile(False)
+        ver.close()
+        R = batch * nodes
+        d, F, V, qkv_n = cfg.d_model, cfg.d_ffn, cfg.vocab, (cfg.n_heads + 2 * cfg.n_kv_heads) * cfg.head_dim
+        shapes = {"gemm_qkv": (qkv_n, d, 2), "gemm_o": (d, cfg.n_heads * cfg.head_dim, 1), "gemm_gate_up": (2 * F, d, 2),
+                  "gemm_down": (d, F, 1), "gemm_lm_head": (V, d, 2)}
+        per = {}
+        useful = executed = ms_total = 0.0
+        for c, (N, K, planes) in shapes.items():
+            ms, n = prof[c]
+            fl = 2.0 * R * N * K * n
+            per[c] = {"us_per_launch": round(ms / n * 1e3, 1), "executed_tflops": round(planes * fl / (ms * 1e-3) / 1e12, 1)}
+            useful += fl
+            executed += planes * fl
+            ms_total += ms
+        out.append({"workload": label, "rows": R, "executed_tflops": executed / (ms_total * 1e-3) / 1e12,
+                    "useful_tflops": useful / (ms_total * 1e-3) / 1e12, "by_class": per})
+    best = max(out, key=lambda o: o["executed_tflops"])
+    return {"bound": "mfma", "kernel": "gemm_large_kernel (128 features x 256 rows per workgroup), all projections of a step",
+            "achieved": best["executed_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": best["executed_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "cases": out}
+
+
 def cpu_baseline(di, wl, parent, token, budget_layers=16):
     """The fp64 oracle on a bounded sample: the 64-row tree step of a 16-layer slice of the model
     against a 1024-key prefix (random K/V stand in for the prefix; timing does not depend on values),
@@ -192,6 +240,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn", action="store_true")
+    ap.add_argument("--no-large-rows", action="store_true")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: a 1 GiB torch copy (calibration), 2 verify steps and 2 attention-only "
                          "launches, nothing else")
@@ -308,6 +357,8 @@ def main():
     }
     if not args.no_attn:
         out["roofline_tree_attention"] = attention_only_bench(di)
+    if not args.no_large_rows:
+        out["roofline_large_rows"] = large_rows_bench(di)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(di, wl, parent, token)
     print(json.dumps(out), flush=True)

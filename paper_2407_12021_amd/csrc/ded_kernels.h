@@ -110,7 +110,8 @@ struct GemmEpilogue {
 // plan.splits slices of part_stride >= rows_pad * round_up(N, 64) floats, `counters` one zeroed int per output tile (left zeroed).
 // Returns false (nothing launched) on an unsupported shape.
 struct GemmPlan {
-  int nwn;     // 0: stream kernel (one feature group per workgroup); 2..4: wide kernel, groups per workgroup
+  int nwn;     // 0: stream kernel (one feature group per workgroup); 2..4: wide kernel, groups per workgroup;
+               // 8: large-row kernel (2 feature groups x 4 row groups per workgroup)
   int nw;      // stream kernel: wavefronts splitting the k range
   int splits;  // split-K slices
 };

@@ -647,6 +647,139 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   DED_STAMP(7)
 }
 
+// ------------------------------------------------------------------------------------------
+// Large-row kernel (rows_pad >= 256: batched trees).  With hundreds of rows per weight the projection is
+// bound by the matrix cores, not by the weight stream, so this is an ordinary tiled GEMM on the same
+// fragment layouts: a workgroup of 8 wavefronts owns 2 feature groups x 4 row groups (128 features x 256
+// rows), wavefront (fg, rg) the 64 x 64 tile the other kernels also give a wavefront, so the split-K
+// hand-over and the epilogues are shared.  Per k step the workgroup stages 8 KiB of weights and 16 / 32
+// KiB of activations through LDS (double buffered; global loads run two k steps ahead in registers), and
+// every fragment read from LDS feeds 4 (weights) or 4 x PLANES / 4 (activations) matrix instructions.
+// ------------------------------------------------------------------------------------------
+__device__ inline float ssq_direct(const GemmEpilogue& e, int rb0, int lane) {
+  if (!e.ssq_in) return 1.f;
+  const float2* p = reinterpret_cast<const float2*>(e.ssq_in + (int64_t)(rb0 * 16 + lane) * e.ssq_groups);
+  float s = 0.f;
+#pragma unroll 8
+  for (int g = 0; g < (e.ssq_groups >> 1); ++g) s += p[g].x + p[g].y;
+  return 1.0f / sqrtf(s * e.inv_k + e.eps);
+}
+
+template <int PLANES, int EPI>
+__global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ part, int64_t part_stride,
+                                                         const uint4* __restrict__ xp, const uint4* __restrict__ wp,
+                                                         int RB, int N, int KT, int splits,
+                                                         int* __restrict__ counters, GemmEpilogue epi) {
+  constexpr int W_U4 = 2 * TN * 64;                 // weights of one k step: 2 feature groups
+  constexpr int X_U4 = 16 * PLANES * 64;            // activations of one k step: 16 row blocks
+  constexpr int STAGE_U4 = W_U4 + X_U4;
+  constexpr int NU = STAGE_U4 / 512;                // staged units per thread (5 or 3)
+  static_assert(STAGE_U4 % 512 == 0, "stage must divide evenly over the workgroup");
+  __shared__ uint4 lds[2][STAGE_U4];
+  __shared__ int s_flag;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fg = wave & 1, rg = wave >> 1;
+  const int NG = (N + 16 * TN - 1) / (16 * TN);
+  const int ng_raw = blockIdx.x * 2 + fg;
+  const int ng = ng_raw < NG ? ng_raw : NG - 1;
+  const int split = blockIdx.y;
+  const int rb_tile = blockIdx.z * 16;
+  const int rbw = rb_tile + rg * 4;                 // first row block of this wavefront
+  const bool valid = ng_raw < NG && rbw < RB;
+  const int groups = KT / PD;
+  const int k_begin = (int)((int64_t)split * groups / splits) * PD;
+  const int k_end = (int)((int64_t)(split + 1) * groups / splits) * PD;  // >= k_begin + 4
+
+  // staged units of a thread: unit 0 is a weight unit (W_U4 == workgroup size), units 1.. are activations
+  static_assert(W_U4 == 512, "unit 0 of every thread must be the weight unit");
+  const int g_raw = blockIdx.x * 2 + (tid >> 8);
+  const uint4* wsrc = wp + (((int64_t)(g_raw < NG ? g_raw : NG - 1) * KT * TN) << 6) + (tid & 255);
+  const int64_t xstride = (int64_t)RB << 7;
+  int xoff[NU - 1];  // offset inside one k step's activation block
+#pragma unroll
+  for (int i = 0; i + 1 < NU; ++i) {
+    const int xu = tid + i * 512;
+    const int rbl = xu / (PLANES * 64), rem = xu - rbl * (PLANES * 64);
+    const int rb = rb_tile + rbl < RB ? rb_tile + rbl : RB - 1;  // ragged last row tile: re-read a valid block
+    xoff[i] = (rb * 2 + rem / 64) * 64 + (rem & 63);
+  }
+  struct Stage {  // named members keep the staged units in registers (w: weights, x1..x4: activations)
+    uint4 w, x1, x2, x3, x4;
+  };
+  static_assert(NU == 3 || NU == 5, "one weight unit and 2 or 4 activation units per thread");
+  auto load_stage = [&](int kt) {
+    Stage st;
+    st.w = wsrc[(int64_t)kt * (TN << 6)];
+    const uint4* xk = xp + kt * xstride;
+    st.x1 = xk[xoff[0]];
+    st.x2 = xk[xoff[1]];
+    if constexpr (NU == 5) {
+      st.x3 = xk[xoff[2]];
+      st.x4 = xk[xoff[3]];
+    }
+    return st;
+  };
+  auto store_stage = [&](int buf, const Stage& st) {
+    uint4* d = lds[buf] + tid;
+    d[0] = st.w;
+    d[512] = st.x1;
+    d[1024] = st.x2;
+    if constexpr (NU == 5) {
+      d[1536] = st.x3;
+      d[2048] = st.x4;
+    }
+  };
+
+  Acc acc;
+#pragma unroll
+  for (int t = 0; t < TN; ++t)
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](int buf) {
+    const uint4* lw = lds[buf] + fg * (TN * 64) + lane;
+    const uint4* lx = lds[buf] + W_U4 + rg * (4 * PLANES * 64) + lane;
+    f16x8_t b[4 * PLANES];
+#pragma unroll
+    for (int i = 0; i < 4 * PLANES; ++i) b[i] = __builtin_bit_cast(f16x8_t, lx[i << 6]);
+#pragma unroll
+    for (int p = 0; p < PLANES; ++p)
+#pragma unroll
+      for (int t = 0; t < TN; ++t) {
+        f16x8_t a = __builtin_bit_cast(f16x8_t, lw[t << 6]);
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+          acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[rb * PLANES + p], acc[t][rb], 0, 0, 0);
+      }
+  };
+
+  // k_end - k_begin >= 4 steps.  Stage k + 2 is fetched while step k is computed and step k + 1 is parked.
+  Stage s0 = load_stage(k_begin);
+  Stage s1 = load_stage(k_begin + 1);
+  store_stage(0, s0);
+  __syncthreads();
+  int buf = 0;
+  for (int kt = k_begin; kt + 2 < k_end; ++kt) {
+    Stage s2 = load_stage(kt + 2);
+    compute(buf);
+    store_stage(buf ^ 1, s1);
+    __syncthreads();
+    s1 = s2;
+    buf ^= 1;
+  }
+  compute(buf);  // step k_end - 2
+  store_stage(buf ^ 1, s1);
+  __syncthreads();
+  compute(buf ^ 1);  // step k_end - 1
+
+  const float row_scale = ssq_direct(epi, rbw < RB ? rbw : 0, lane);
+  if (splits == 1) {
+    if (valid) run_epilogue<EPI, 4>(epi, ng, N, rbw, rbw, row_scale, lane, acc);
+  } else if (finish_split(part, part_stride, split, splits, counters, NG, ng, rbw, lane, valid, acc, &s_flag) && valid) {
+    load_slices<4>(part, part_stride, splits, NG, ng, rbw, 0, lane, acc);
+    run_epilogue<EPI, 4>(epi, ng, N, rbw, rbw, row_scale, lane, acc);
+  }
+}
+
 // Debug knob: DED_GEMM_TUNE="nwn,splits" forces the kernel shape (nwn 0 = stream kernel).
 struct Tune {
   int nwn = -1, splits = 0;
@@ -678,6 +811,11 @@ bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float*
                   int nw, hipStream_t s) {
   const int splits = plan.splits;
 #define DED_ARGS part, part_stride, xp, wp, RB, N, KT, splits, counters, epi
+  if (plan.nwn == 8) {
+    dim3 grid((((N + 16 * TN - 1) / (16 * TN)) + 1) / 2, splits, (RB + 15) / 16);
+    hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI>), grid, dim3(512), 0, s, DED_ARGS);
+    return true;
+  }
   if (plan.nwn == 0) {
     if (nw == 4) hipLaunchKernelGGL((gemm_stream_kernel<4, PLANES, EPI>), grid_stream, dim3(256), 0, s, DED_ARGS);
     else if (nw == 2) hipLaunchKernelGGL((gemm_stream_kernel<2, PLANES, EPI>), grid_stream, dim3(128), 0, s, DED_ARGS);
@@ -698,6 +836,12 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
   static const Tune tune;
   const int NG = (N + 16 * TN - 1) / (16 * TN), groups = K / (32 * PD), rg = rows_pad / 64;
   const int64_t w_bytes = (int64_t)NG * 64 * K * 2, slice = (int64_t)rows_pad * N * 4;
+  if (rows_pad >= 256) {  // matrix-core bound: the large-row kernel; split k only to fill the chip
+    const int tiles = ((NG + 1) / 2) * ((rows_pad + 255) / 256);
+    int s = 1;
+    while (s < 8 && s < max_splits && s < groups && tiles * s < (kCUs * 3) / 4) ++s;
+    return GemmPlan{8, 1, s};
+  }
   GemmPlan best{0, 1, 1};
   double best_cost = 1e300;
   for (int nwn = 0; nwn <= 4; ++nwn) {
@@ -730,6 +874,7 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
 
 int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan) {
   const int NG = (N + 16 * TN - 1) / (16 * TN);
+  if (plan.nwn == 8) return ((NG + 1) / 2) * ((rows_pad + 255) / 256);
   const int gx = plan.nwn == 0 ? NG : (NG + plan.nwn - 1) / plan.nwn;
   return gx * (rows_pad / 64);
 }
@@ -742,7 +887,7 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
   const int NG = (N + 16 * TN - 1) / (16 * TN);
   const int splits = plan.splits;
   if (splits < 1 || splits > groups || !counters) return false;
-  if (plan.nwn != 0 && groups / splits < 2) return false;
+  if (plan.nwn != 0 && plan.nwn != 8 && groups / splits < 2) return false;
   if (splits > 1 && part_stride < (int64_t)rows_pad * NG * 16 * TN) return false;
   if ((epi.kind == EPI_RESIDUAL || epi.kind == EPI_QKV || epi.kind == EPI_SILU) && N % 64) return false;
   int nw = plan.nw >= 4 ? 4 : plan.nw >= 2 ? 2 : 1;
