@@ -650,11 +650,11 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
 // ------------------------------------------------------------------------------------------
 // Large-row kernel (rows_pad >= 256: batched trees).  With hundreds of rows per weight the projection is
 // bound by the matrix cores, not by the weight stream, so this is an ordinary tiled GEMM on the same
-// fragment layouts: a workgroup of 8 wavefronts owns 2 feature groups x 4 row groups (128 features x 256
-// rows), wavefront (fg, rg) the 64 x 64 tile the other kernels also give a wavefront, so the split-K
-// hand-over and the epilogues are shared.  Per k step the workgroup stages 8 KiB of weights and 16 / 32
-// KiB of activations through LDS (double buffered; global loads run two k steps ahead in registers), and
-// every fragment read from LDS feeds 4 (weights) or 4 x PLANES / 4 (activations) matrix instructions.
+// fragment layouts: a workgroup of 8 wavefronts owns FGS feature groups x RGS row groups (FGS * RGS == 8;
+// 4 x 2 = 256 features x 128 rows), wavefront (fg, rg) the 64 x 64 tile the other kernels also give a
+// wavefront, so the split-K hand-over and the epilogues are shared.  A stage holds CH k steps of the
+// workgroup's weights and activations in LDS (double buffered, one barrier per stage; global loads run two
+// stages ahead in registers); every weight fragment read from LDS feeds 4 matrix instructions per plane.
 // ------------------------------------------------------------------------------------------
 __device__ inline float ssq_direct(const GemmEpilogue& e, int rb0, int lane) {
   if (!e.ssq_in) return 1.f;
@@ -665,70 +665,81 @@ __device__ inline float ssq_direct(const GemmEpilogue& e, int rb0, int lane) {
   return 1.0f / sqrtf(s * e.inv_k + e.eps);
 }
 
+constexpr int LARGE_FGS = 4, LARGE_RGS = 2, LARGE_CH = 2;
+
 template <int PLANES, int EPI>
 __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ part, int64_t part_stride,
                                                          const uint4* __restrict__ xp, const uint4* __restrict__ wp,
                                                          int RB, int N, int KT, int splits,
                                                          int* __restrict__ counters, GemmEpilogue epi) {
-  constexpr int W_U4 = 2 * TN * 64;                 // weights of one k step: 2 feature groups
-  constexpr int X_U4 = 16 * PLANES * 64;            // activations of one k step: 16 row blocks
-  constexpr int STAGE_U4 = W_U4 + X_U4;
-  constexpr int NU = STAGE_U4 / 512;                // staged units per thread (5 or 3)
-  static_assert(STAGE_U4 % 512 == 0, "stage must divide evenly over the workgroup");
+  constexpr int FGS = LARGE_FGS, RGS = LARGE_RGS, CH = LARGE_CH;
+  static_assert(FGS * RGS == 8, "8 wavefronts");
+  constexpr int W_U4 = FGS * TN * 64;               // weights of one k step
+  constexpr int X_U4 = RGS * 4 * PLANES * 64;       // activations of one k step
+  constexpr int STEP_U4 = W_U4 + X_U4;
+  constexpr int STAGE_U4 = CH * STEP_U4;
+  constexpr int UPS = STEP_U4 / 512;                // staged units per thread and k step
+  constexpr int WUPS = W_U4 / 512;                  // ... of which weights (the first ones)
+  constexpr int NU = CH * UPS;
+  static_assert(STEP_U4 % 512 == 0 && W_U4 % 512 == 0 && NU <= 8, "units must not straddle operand kinds");
+  static_assert(PD % CH == 0, "a k range holds whole stages");
   __shared__ uint4 lds[2][STAGE_U4];
   __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int fg = wave & 1, rg = wave >> 1;
+  const int fg = wave % FGS, rg = wave / FGS;
   const int NG = (N + 16 * TN - 1) / (16 * TN);
-  const int ng_raw = blockIdx.x * 2 + fg;
+  const int ng_raw = blockIdx.x * FGS + fg;
   const int ng = ng_raw < NG ? ng_raw : NG - 1;
   const int split = blockIdx.y;
-  const int rb_tile = blockIdx.z * 16;
+  const int rb_tile = blockIdx.z * (RGS * 4);
   const int rbw = rb_tile + rg * 4;                 // first row block of this wavefront
   const bool valid = ng_raw < NG && rbw < RB;
   const int groups = KT / PD;
   const int k_begin = (int)((int64_t)split * groups / splits) * PD;
-  const int k_end = (int)((int64_t)(split + 1) * groups / splits) * PD;  // >= k_begin + 4
+  const int k_end = (int)((int64_t)(split + 1) * groups / splits) * PD;
+  const int n_stages = (k_end - k_begin) / CH;      // >= PD / CH >= 2
 
-  // staged units of a thread: unit 0 is a weight unit (W_U4 == workgroup size), units 1.. are activations
-  static_assert(W_U4 == 512, "unit 0 of every thread must be the weight unit");
-  const int g_raw = blockIdx.x * 2 + (tid >> 8);
-  const uint4* wsrc = wp + (((int64_t)(g_raw < NG ? g_raw : NG - 1) * KT * TN) << 6) + (tid & 255);
-  const int64_t xstride = (int64_t)RB << 7;
-  int xoff[NU - 1];  // offset inside one k step's activation block
+  // Unit i of a thread (u = tid + 512 i inside a stage): k step i / UPS of the stage; inside the step the
+  // first WUPS units are weights, the others activations (the kind depends on i only).  off[i] = offset of
+  // the unit from the operand's address at the stage's first k step.
+  const int64_t xstride = (int64_t)RB << 7;         // activations of one k step (all row blocks, 2 planes)
+  int64_t off[NU];
 #pragma unroll
-  for (int i = 0; i + 1 < NU; ++i) {
-    const int xu = tid + i * 512;
-    const int rbl = xu / (PLANES * 64), rem = xu - rbl * (PLANES * 64);
-    const int rb = rb_tile + rbl < RB ? rb_tile + rbl : RB - 1;  // ragged last row tile: re-read a valid block
-    xoff[i] = (rb * 2 + rem / 64) * 64 + (rem & 63);
+  for (int i = 0; i < NU; ++i) {
+    const int ks = i / UPS, j = i % UPS;
+    if (j < WUPS) {
+      const int v = tid + j * 512;
+      const int g_raw = blockIdx.x * FGS + (v >> 8);
+      off[i] = ((((int64_t)(g_raw < NG ? g_raw : NG - 1) * KT + ks) * TN) << 6) + (v & 255);
+    } else {
+      const int xu = tid + (j - WUPS) * 512;
+      const int rbl = xu / (PLANES * 64), rem = xu - rbl * (PLANES * 64);
+      const int rb = rb_tile + rbl < RB ? rb_tile + rbl : RB - 1;  // ragged last row tile: re-read a valid block
+      off[i] = ks * xstride + (rb * 2 + rem / 64) * 64 + (rem & 63);
+    }
   }
-  struct Stage {  // named members keep the staged units in registers (w: weights, x1..x4: activations)
-    uint4 w, x1, x2, x3, x4;
+  struct Stage {  // named members keep the staged units in registers
+    uint4 u0, u1, u2, u3, u4, u5, u6, u7;
   };
-  static_assert(NU == 3 || NU == 5, "one weight unit and 2 or 4 activation units per thread");
+#define DED_EACH_UNIT(F) F(0, u0) F(1, u1) F(2, u2) F(3, u3) F(4, u4) F(5, u5) F(6, u6) F(7, u7)
   auto load_stage = [&](int kt) {
     Stage st;
-    st.w = wsrc[(int64_t)kt * (TN << 6)];
+    const uint4* wk = wp + ((int64_t)kt * TN << 6);
     const uint4* xk = xp + kt * xstride;
-    st.x1 = xk[xoff[0]];
-    st.x2 = xk[xoff[1]];
-    if constexpr (NU == 5) {
-      st.x3 = xk[xoff[2]];
-      st.x4 = xk[xoff[3]];
-    }
+#define DED_LOAD(i, m) \
+    if constexpr (i < NU) st.m = ((i % UPS) < WUPS ? wk : xk)[off[i < NU ? i : 0]];
+    DED_EACH_UNIT(DED_LOAD)
+#undef DED_LOAD
     return st;
   };
   auto store_stage = [&](int buf, const Stage& st) {
     uint4* d = lds[buf] + tid;
-    d[0] = st.w;
-    d[512] = st.x1;
-    d[1024] = st.x2;
-    if constexpr (NU == 5) {
-      d[1536] = st.x3;
-      d[2048] = st.x4;
-    }
+#define DED_STORE(i, m) \
+    if constexpr (i < NU) d[i * 512] = st.m;
+    DED_EACH_UNIT(DED_STORE)
+#undef DED_STORE
   };
+#undef DED_EACH_UNIT
 
   Acc acc;
 #pragma unroll
@@ -736,40 +747,43 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   auto compute = [&](int buf) {
-    const uint4* lw = lds[buf] + fg * (TN * 64) + lane;
-    const uint4* lx = lds[buf] + W_U4 + rg * (4 * PLANES * 64) + lane;
-    f16x8_t b[4 * PLANES];
 #pragma unroll
-    for (int i = 0; i < 4 * PLANES; ++i) b[i] = __builtin_bit_cast(f16x8_t, lx[i << 6]);
+    for (int ks = 0; ks < CH; ++ks) {
+      const uint4* lw = lds[buf] + ks * STEP_U4 + fg * (TN * 64) + lane;
+      const uint4* lx = lds[buf] + ks * STEP_U4 + W_U4 + rg * (4 * PLANES * 64) + lane;
+      f16x8_t b[4 * PLANES];
 #pragma unroll
-    for (int p = 0; p < PLANES; ++p)
+      for (int i = 0; i < 4 * PLANES; ++i) b[i] = __builtin_bit_cast(f16x8_t, lx[i << 6]);
 #pragma unroll
-      for (int t = 0; t < TN; ++t) {
-        f16x8_t a = __builtin_bit_cast(f16x8_t, lw[t << 6]);
+      for (int p = 0; p < PLANES; ++p)
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
-          acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[rb * PLANES + p], acc[t][rb], 0, 0, 0);
-      }
+        for (int t = 0; t < TN; ++t) {
+          f16x8_t a = __builtin_bit_cast(f16x8_t, lw[t << 6]);
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
+            acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[rb * PLANES + p], acc[t][rb], 0, 0, 0);
+        }
+    }
   };
 
-  // k_end - k_begin >= 4 steps.  Stage k + 2 is fetched while step k is computed and step k + 1 is parked.
+  // Stage c + 2 is fetched while stage c is computed and stage c + 1 is parked in LDS.
   Stage s0 = load_stage(k_begin);
-  Stage s1 = load_stage(k_begin + 1);
+  Stage s1 = load_stage(k_begin + CH);
   store_stage(0, s0);
   __syncthreads();
   int buf = 0;
-  for (int kt = k_begin; kt + 2 < k_end; ++kt) {
-    Stage s2 = load_stage(kt + 2);
+  for (int c = 0; c + 2 < n_stages; ++c) {
+    Stage s2 = load_stage(k_begin + (c + 2) * CH);
     compute(buf);
     store_stage(buf ^ 1, s1);
     __syncthreads();
     s1 = s2;
     buf ^= 1;
   }
-  compute(buf);  // step k_end - 2
+  compute(buf);  // second-last stage
   store_stage(buf ^ 1, s1);
   __syncthreads();
-  compute(buf ^ 1);  // step k_end - 1
+  compute(buf ^ 1);  // last stage
 
   const float row_scale = ssq_direct(epi, rbw < RB ? rbw : 0, lane);
   if (splits == 1) {
@@ -812,7 +826,7 @@ bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float*
   const int splits = plan.splits;
 #define DED_ARGS part, part_stride, xp, wp, RB, N, KT, splits, counters, epi
   if (plan.nwn == 8) {
-    dim3 grid((((N + 16 * TN - 1) / (16 * TN)) + 1) / 2, splits, (RB + 15) / 16);
+    dim3 grid(((N + 16 * TN - 1) / (16 * TN) + LARGE_FGS - 1) / LARGE_FGS, splits, (RB + 4 * LARGE_RGS - 1) / (4 * LARGE_RGS));
     hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI>), grid, dim3(512), 0, s, DED_ARGS);
     return true;
   }
@@ -837,7 +851,7 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
   const int NG = (N + 16 * TN - 1) / (16 * TN), groups = K / (32 * PD), rg = rows_pad / 64;
   const int64_t w_bytes = (int64_t)NG * 64 * K * 2, slice = (int64_t)rows_pad * N * 4;
   if (rows_pad >= 256) {  // matrix-core bound: the large-row kernel; split k only to fill the chip
-    const int tiles = ((NG + 1) / 2) * ((rows_pad + 255) / 256);
+    const int tiles = ((NG + LARGE_FGS - 1) / LARGE_FGS) * ((rows_pad + 64 * LARGE_RGS - 1) / (64 * LARGE_RGS));
     int s = 1;
     while (s < 8 && s < max_splits && s < groups && tiles * s < (kCUs * 3) / 4) ++s;
     return GemmPlan{8, 1, s};
@@ -874,7 +888,7 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
 
 int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan) {
   const int NG = (N + 16 * TN - 1) / (16 * TN);
-  if (plan.nwn == 8) return ((NG + 1) / 2) * ((rows_pad + 255) / 256);
+  if (plan.nwn == 8) return ((NG + LARGE_FGS - 1) / LARGE_FGS) * ((rows_pad + 64 * LARGE_RGS - 1) / (64 * LARGE_RGS));
   const int gx = plan.nwn == 0 ? NG : (NG + plan.nwn - 1) / plan.nwn;
   return gx * (rows_pad / 64);
 }
