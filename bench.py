@@ -31,12 +31,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
 PMC_FETCH_FACTOR = 2.0
 PMC_WRITE_FACTOR = 1.0
 PMC_KIB = {  # class: (FETCH_SIZE, WRITE_SIZE) mean per launch
-    "gemm_qkv": (59724.1, 14346.0),
-    "gemm_o": (21085.6, 6282.0),
-    "gemm_gate_up": (97837.9, 12394.8),
-    "gemm_down": (52189.9, 6282.0),
-    "gemm_lm_head": (140278.0, 24012.2),
-    "tree_attention_c2": (37511.8, 16640.1),
+    "gemm_qkv": (59748.0, 14346.0),
+    "gemm_o": (21076.0, 6282.0),
+    "gemm_gate_up": (97845.0, 12395.0),
+    "gemm_down": (52181.0, 6282.0),
+    "gemm_lm_head": (140277.0, 24013.0),
+    "tree_attention_c2": (37500.0, 16640.0),
 }
 
 
