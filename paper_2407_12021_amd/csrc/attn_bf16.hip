@@ -62,27 +62,8 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   const int quad = lane >> 4;
   const int g = active ? vr / n_step : 0;
   const int node = active ? vr - g * n_step : 0;
-  // this lane's row of the ancestor bitmask (4 words cover 256 tree slots), kept in registers
-  const uint64_t* mrow = mask + ((int64_t)b * n_step + node) * 4;
-  const uint64_t mw0 = mrow[0], mw1 = mrow[1], mw2 = mrow[2], mw3 = mrow[3];
-
-  f16x8_t q[8];  // [head-dim chunk kk][plane hi / lo]
-  if (active) {
-    const uint4* qsrc = qp + (((int64_t)bz * (VR / 16) + vrb) * 8 << 6) + lane;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, qsrc[i << 6]);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, make_uint4(0, 0, 0, 0));
-  }
-
   const uint4* kbase = kc + (int64_t)bz * cap * 16;  // 16 uint4 per key
   const uint4* vbase = vc + (int64_t)bz * cap * 16;
-
-  f32x4_t o[8];
-#pragma unroll
-  for (int hb = 0; hb < 8; ++hb) o[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float m_run = NEG_BIG, l_run = 0.f;
 
   // global -> register -> LDS staging of one tile (kept in eight named registers per thread)
   struct Stage {
@@ -102,6 +83,29 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     st.v3 = vs[768];
     return st;
   };
+  // the first tile is requested before anything else (mask row, queries): it has the longest way to come
+  Stage st_first;
+  if (t_begin < t_end) st_first = load_tile(t_begin);
+
+  // this lane's row of the ancestor bitmask (4 words cover 256 tree slots), kept in registers
+  const uint64_t* mrow = mask + ((int64_t)b * n_step + node) * 4;
+  const uint64_t mw0 = mrow[0], mw1 = mrow[1], mw2 = mrow[2], mw3 = mrow[3];
+
+  f16x8_t q[8];  // [head-dim chunk kk][plane hi / lo]
+  if (active) {
+    const uint4* qsrc = qp + (((int64_t)bz * (VR / 16) + vrb) * 8 << 6) + lane;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, qsrc[i << 6]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, make_uint4(0, 0, 0, 0));
+  }
+
+  f32x4_t o[8];
+#pragma unroll
+  for (int hb = 0; hb < 8; ++hb) o[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = NEG_BIG, l_run = 0.f;
+
   auto store_tile = [&](int buf, const Stage& st) {
     uint4* d = lds[buf] + tid;
     d[0] = st.k0;
@@ -192,7 +196,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
 
   DED_ASTAMP(0)
   if (t_begin < t_end) {
-    store_tile(0, load_tile(t_begin));
+    store_tile(0, st_first);
     __syncthreads();
     DED_ASTAMP(1)
     int buf = 0;
