@@ -5,7 +5,9 @@ Only the tests, the smoke check and the benchmark's cpu_baseline leg may import 
 product path never does.
 
 Pinned parts (see tests/test_oracle_pins.py): every function below is pinned by closed forms,
-library special cases, brute force on tiny trees or the chain == autoregressive invariant.
+library special cases, brute force on tiny trees or the chain == autoregressive invariant; the
+pseudo-sequence builder by the set of root-to-node paths, hand-worked cases and the equality of a
+candidate's logits in the merged tree and in its own chain.
 Parity unpinned: none.
 """
 from .decoder import (  # noqa: F401
@@ -13,3 +15,4 @@ from .decoder import (  # noqa: F401
     forward_rows, prefill, verify_tree, autoregressive_logits, autoregressive_decode,
 )
 from .accept import argmax_margin, accept_walk, compact_rows  # noqa: F401
+from .trie import build_trie  # noqa: F401

@@ -359,3 +359,108 @@ def test_planted_tree_and_lossless_multi_step(small_cfg, small_model):
     _, fk, fv = oracle.prefill(cfg, w, seq)
     for l in range(cfg.n_layers):
         assert np.allclose(pk[l], fk[l], atol=1e-10) and np.allclose(pv[l], fv[l], atol=1e-10)
+
+
+# ---------------------------------------------------------------------------------------------
+# Pseudo-sequence (trie) builder of Sec. 2.4
+# ---------------------------------------------------------------------------------------------
+
+
+def _trie_cases():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "trie_cases.txt")
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        left, right = line.split("->")
+        root = int(left.split("cands:")[0].split("root:")[1])
+        rest = left.split("cands:")[1]
+        max_nodes = None
+        if "max:" in rest:
+            rest, m = rest.split("max:")
+            max_nodes = int(m)
+        cands = [[int(x) for x in c.split()] for c in rest.split("|")] if rest.strip() else []
+        parent = [int(x) for x in right.split("token:")[0].split("parent:")[1].split()]
+        token = [int(x) for x in right.split("token:")[1].split("end:")[0].split()]
+        end = [int(x) for x in right.split("end:")[1].split()]
+        yield root, cands, max_nodes, parent, token, end
+
+
+def test_trie_hand_worked_cases():
+    n = 0
+    for root, cands, max_nodes, parent, token, end in _trie_cases():
+        got = oracle.build_trie(root, cands, max_nodes)
+        assert got == (parent, token, end), (root, cands, max_nodes, got)
+        n += 1
+    assert n == 7
+
+
+def _paths(parent, token):
+    out = []
+    for i in range(len(parent)):
+        p, j = [], i
+        while j > 0:
+            p.append(token[j])
+            j = parent[j]
+        out.append(tuple(reversed(p)))
+    return out
+
+
+def test_trie_is_the_set_of_distinct_prefixes():
+    """Brute force: the root-to-node token paths are exactly the distinct prefixes of the candidates
+    (each once), every candidate ends at the node that spells it, parents precede children and no
+    two siblings carry the same token."""
+    g = np.random.default_rng(11)
+    for trial in range(200):
+        n_c = int(g.integers(0, 9))
+        cands = [list(g.integers(0, 4, size=int(g.integers(0, 6)))) for _ in range(n_c)]
+        parent, token, end = oracle.build_trie(5, cands)
+        paths = _paths(parent, token)
+        want = {()} | {tuple(int(t) for t in c[:k]) for c in cands for k in range(1, len(c) + 1)}
+        assert len(paths) == len(set(paths)) == len(want) and set(paths) == want
+        assert parent[0] == -1 and all(0 <= parent[i] < i for i in range(1, len(parent)))
+        assert [paths[e] for e in end] == [tuple(int(t) for t in c) for c in cands]
+        sib = [(parent[i], token[i]) for i in range(1, len(parent))]
+        assert len(sib) == len(set(sib))
+        # first appearance order: inserting the candidates one by one only ever appends nodes
+        for k in range(n_c + 1):
+            pk, tk, _ = oracle.build_trie(5, cands[:k])
+            assert pk == parent[:len(pk)] and tk == token[:len(tk)]
+
+
+def test_trie_budget_keeps_a_prefix_of_the_unbounded_tree():
+    g = np.random.default_rng(12)
+    for trial in range(100):
+        cands = [list(g.integers(0, 3, size=int(g.integers(1, 6)))) for _ in range(int(g.integers(1, 8)))]
+        full = oracle.build_trie(1, cands)
+        m = int(g.integers(1, len(full[0]) + 2))
+        parent, token, end = oracle.build_trie(1, cands, m)
+        assert len(parent) == min(m, len(full[0]))
+        paths_full = set(_paths(full[0], full[1]))
+        paths = _paths(parent, token)
+        assert set(paths) <= paths_full and len(set(paths)) == len(paths)
+        for c, e in zip(cands, end):  # a candidate stops at its longest prefix that is in the tree
+            c = tuple(int(t) for t in c)
+            assert paths[e] == c[:len(paths[e])]
+            assert len(paths[e]) == len(c) or c[:len(paths[e]) + 1] not in set(paths)
+
+
+def test_candidate_in_merged_tree_equals_its_own_chain(small_cfg, small_model):
+    """The purpose of the pseudo-sequence: verifying the merged tree gives, at every node of a
+    candidate, the logits that verifying that candidate alone (a chain) gives."""
+    cfg, w = small_cfg, small_model
+    g = np.random.default_rng(13)
+    prefix = g.integers(0, cfg.vocab, size=9)
+    _, pk, pv = oracle.prefill(cfg, w, prefix)
+    cands = [[3, 5, 8], [3, 5, 2, 7], [3, 1], [4, 4, 4]]
+    parent, token, end = oracle.build_trie(11, cands)
+    logits, _, _ = oracle.verify_tree(cfg, w, np.array(parent), np.array(token), pk, pv)
+    for c, e in zip(cands, end):
+        chain = np.arange(-1, len(c))
+        ref, _, _ = oracle.verify_tree(cfg, w, chain, np.array([11] + c), pk, pv)
+        node, path = e, []
+        while node >= 0:
+            path.append(node)
+            node = parent[node]
+        np.testing.assert_allclose(logits[path[::-1]], ref, rtol=0, atol=1e-10)
