@@ -104,6 +104,60 @@ def time_steps(ver, P, parent, tokens_list, steps, warmup):
     return dt, n_tok
 
 
+def decode_loop_bench(di, ver, wl, prefix, root, n_new=48, seed=2):
+    """End-to-end decoding from the resident 1024-token prefix: every step builds 24 candidate continuations
+    of length 4 (the paper's n and l) from the synthetic tri-gram model, merges them with ded_build_tree
+    (budget = the context's 64 nodes), verifies the tree and commits the accepted tokens.  As a random-init
+    model never agrees with tri-gram drafts, the first candidate carries the model's own continuation (from
+    a plain one-token-per-step pass through the same library) for m ~ Geometric tokens.  The output must
+    equal that plain greedy continuation token for token."""
+    import numpy as np
+    from paper_2407_12021_amd import binding as B
+    P = len(prefix)
+    ref, r, p = [], int(root), P
+    while len(ref) < n_new + wl.depth + 8:  # plain greedy decoding
+        ver.verify_step([p], [[-1]], [[r]])
+        acc, _, newp = ver.accept(mode=0)
+        r, p = acc[0][0], newp[0]
+        ref.append(r)
+    tri = di.SyntheticTrigram(wl.model.vocab, seed=0)
+    g = np.random.default_rng(seed)
+    out, steps, nodes = [], 0, 0
+    prev, r, p = int(prefix[-1]), int(root), P
+    t_build = 0.0
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while len(out) < n_new:
+        tb = time.perf_counter()
+        cands = []
+        for c in range(24):
+            a, b, seq = prev, r, []
+            for _ in range(4):
+                succ, prob = tri.successors(a, b)
+                t = int(succ[g.choice(len(succ), p=prob)])
+                seq.append(t)
+                a, b = b, t
+            cands.append(seq)
+        m = min(int(g.geometric(0.42)) - 1, 4)
+        cands[0] = ref[len(out):len(out) + m] + cands[0][m:]
+        rc, parent, token, _ = B.ded_build_tree(r, cands, wl.n_nodes)
+        assert rc == B.DED_OK
+        t_build += time.perf_counter() - tb
+        ver.verify_step([p], [parent], [token])
+        acc, _, newp = ver.accept(mode=0)
+        out += acc[0]
+        prev = acc[0][-2] if len(acc[0]) > 1 else r
+        r, p = acc[0][-1], newp[0]
+        steps += 1
+        nodes += len(parent)
+    dt = time.perf_counter() - t0
+    lossless = out[:n_new] == ref[:n_new]
+    return {"tokens": len(out), "steps": steps, "tokens_per_s": len(out) / dt, "steps_per_s": steps / dt,
+            "mean_accepted_per_step": len(out) / steps, "mean_tree_nodes": nodes / steps,
+            "host_draft_and_tree_build_share": t_build / dt, "lossless_vs_plain_greedy": bool(lossless)}
+
+
 def attention_only_bench(di, iters=40):
     """Tree attention alone on the attention-only configuration; 8 layers act as rotating K/V buffer
     sets (8 x 68 MB > the 256 MB last-level cache) so that every launch streams from HBM."""
@@ -292,6 +346,8 @@ def main():
     dt_raw, n_tok_raw = time_steps(ver, P, parent, [token], max(5, args.steps // 4), 1)
     raw_steps = max(5, args.steps // 4)
 
+    decode = decode_loop_bench(di, ver, wl, prefix, int(token[0]))
+
     # per-kernel-class times (separate pass: event brackets add overhead)
     ver.profile(True)
     prof_steps = 5
@@ -339,6 +395,7 @@ def main():
         "acceptance": "planted: one branch carries the model's own continuation for m~Geom tokens",
         "raw_trigram_tree": {"steps_per_s": raw_steps / dt_raw, "verified_tokens_per_s": n_tok_raw / dt_raw,
                              "mean_accepted_per_step": n_tok_raw / raw_steps},
+        "decode_loop": decode,
         "kernel_ms_per_step": kernels_ms,
         "roofline": {"bound": "hbm",
                      "kernel": "gate/up projection GEMM with SiLU*up epilogue (gemm_wide_kernel, 3 feature groups per "

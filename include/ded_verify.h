@@ -102,6 +102,24 @@ size_t ded_kv_layer_bytes(const ded_config *cfg);
 int ded_validate_tree(const ded_config *cfg, int32_t batch, const int32_t *prefix_len,
                       const int32_t *n_nodes, const int32_t *parent, const int32_t *token);
 
+/* Pseudo-sequence of Sec. 2.4 (Draft Construction and Verification): merges ranked candidate
+ * continuations of the last committed token into one tree in which every candidate is a root-to-node
+ * path and every common prefix appears once - the input ded_verify_step takes.  Host only, touches
+ * no device.
+ *   root_token   the last committed token (node 0)
+ *   n_cand       number of candidates, in rank order; cand_len [n_cand] their lengths (0..max_len)
+ *   cand_tokens  host [n_cand][max_len] token ids (entries past cand_len are ignored)
+ *   max_nodes    node budget (>= 1, root included): a candidate is cut where the budget runs out,
+ *                later candidates still follow nodes that exist
+ *   parent, token  host outputs [max_nodes]; nodes are numbered in order of first appearance, so
+ *                  parent[0] = -1 and 0 <= parent[i] < i
+ *   cand_end     host output [n_cand] or NULL: the node where candidate c ends (or was cut)
+ *   n_nodes      host output: nodes written
+ * Errors: DED_EINVAL (null output, negative sizes, a length above max_len). */
+int ded_build_tree(int32_t root_token, int32_t n_cand, const int32_t *cand_len, const int32_t *cand_tokens,
+                   int32_t max_len, int32_t max_nodes, int32_t *parent, int32_t *token,
+                   int32_t *cand_end, int32_t *n_nodes);
+
 /* Creates a context: validates cfg, re-lays out the weights into `workspace` (device, 256-byte
  * aligned, >= ded_workspace_bytes) on `hip_stream` (a hipStream_t; NULL = the default stream) and
  * waits for that to finish.  The workspace and KV buffers must outlive the context; their contents

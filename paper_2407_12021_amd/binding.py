@@ -20,7 +20,7 @@ DED_OK, DED_EINVAL, DED_ETREE, DED_ETOKEN, DED_ECAP, DED_ESTATE, DED_EHIP, DED_E
 DED_F32, DED_BF16 = 0, 1
 
 EXPORTS = [
-    "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_verify_init", "ded_verify_free",
+    "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_build_tree", "ded_verify_init", "ded_verify_free",
     "ded_verify_step", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
     "ded_profile_enable", "ded_profile_read", "ded_strerror",
 ]
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.ded_kv_layer_bytes.argtypes = [C.POINTER(ded_config)]
         L.ded_validate_tree.restype = C.c_int
         L.ded_validate_tree.argtypes = [C.POINTER(ded_config), C.c_int32, i32p, i32p, i32p, i32p]
+        L.ded_build_tree.restype = C.c_int
+        L.ded_build_tree.argtypes = [C.c_int32, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
         L.ded_verify_init.restype = C.c_int
         L.ded_verify_init.argtypes = [C.POINTER(ded_config), C.POINTER(ded_weights), C.POINTER(ded_kv), vp,
                                       C.c_size_t, vp, C.POINTER(vp)]
@@ -130,6 +132,24 @@ def ded_validate_tree(cfg: ded_config, prefix_len, n_nodes, parent, token) -> in
     par = None if parent is None else _i32(parent)
     tok = None if token is None else _i32(token)
     return int(lib().ded_validate_tree(C.byref(cfg), len(pl), _p32(pl), _p32(nn), _p32(par), _p32(tok)))
+
+
+def ded_build_tree(root_token: int, candidates, max_nodes: int):
+    """candidates: ranked sequences of token ids.  Returns (rc, parent, token, cand_end) with parent / token
+    cut to the nodes written."""
+    n = len(candidates)
+    lens = _i32([len(c) for c in candidates]) if n else np.zeros(1, np.int32)
+    max_len = int(max([len(c) for c in candidates], default=0))
+    toks = np.zeros((max(n, 1), max(max_len, 1)), np.int32)
+    for i, c in enumerate(candidates):
+        toks[i, : len(c)] = np.asarray(c, dtype=np.int32)
+    parent = np.zeros(max(max_nodes, 1), np.int32)
+    token = np.zeros(max(max_nodes, 1), np.int32)
+    end = np.zeros(max(n, 1), np.int32)
+    nn = C.c_int32(0)
+    rc = int(lib().ded_build_tree(int(root_token), n, _p32(lens), _p32(toks), max(max_len, 1) if n else 0, int(max_nodes),
+                                  _p32(parent), _p32(token), _p32(end), C.byref(nn)))
+    return rc, parent[: nn.value].copy(), token[: nn.value].copy(), end[:n].copy()
 
 
 def ded_verify_init(cfg: ded_config, weights: ded_weights, kv: ded_kv, workspace_ptr: int, workspace_bytes: int,

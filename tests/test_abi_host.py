@@ -88,3 +88,60 @@ def test_init_rejects_bad_arguments_before_touching_the_device(b):
     assert b.lib().ded_accept(None, 0, None, None, None, None) == b.DED_EINVAL
     assert b.lib().ded_verify_step(None, 1, None, None, None, None, None) == b.DED_EINVAL
     assert "tree" in b.ded_strerror(b.DED_ETREE)
+
+
+# ---------------------------------------------------------------------------------------------
+# ded_build_tree (host only): the pseudo-sequence builder against the oracle, bit-exact
+# ---------------------------------------------------------------------------------------------
+
+
+def test_build_tree_matches_oracle_bit_exact():
+    import numpy as np
+    import oracle
+    from paper_2407_12021_amd import binding as B
+    g = np.random.default_rng(21)
+    for trial in range(300):
+        n_c = int(g.integers(0, 30))
+        vocab = int(g.choice([2, 3, 50, 32000]))
+        cands = [list(map(int, g.integers(0, vocab, size=int(g.integers(0, 7))))) for _ in range(n_c)]
+        budget = int(g.choice([1, 2, 5, 16, 64, 256]))
+        rc, parent, token, end = B.ded_build_tree(9, cands, budget)
+        assert rc == B.DED_OK
+        ref = oracle.build_trie(9, cands, budget)
+        assert (parent.tolist(), token.tolist(), end.tolist()) == ref
+
+
+def test_build_tree_paper_shape_and_validation():
+    """24 candidates of length 4 (the paper's n and l, Detailed Experimental Settings): the tree fits the
+    97-node budget, is a valid input of the verification step, and every candidate is one of its paths."""
+    import numpy as np
+    import ded_inputs as di
+    import oracle
+    from paper_2407_12021_amd import binding as B
+    tri = di.SyntheticTrigram(32000, seed=0)
+    g = np.random.default_rng(5)
+    prev, root = 17, 4711
+    cands = []
+    for _ in range(24):
+        a, b, seq = prev, root, []
+        for _ in range(4):
+            succ, prob = tri.successors(a, b)
+            t = int(succ[g.choice(len(succ), p=prob)])
+            seq.append(t)
+            a, b = b, t
+        cands.append(seq)
+    rc, parent, token, end = B.ded_build_tree(root, cands, 1 + 24 * 4)
+    assert rc == B.DED_OK and len(parent) <= 97
+    assert (parent.tolist(), token.tolist(), end.tolist()) == oracle.build_trie(root, cands, 97)
+    cfg = B.make_config(2, 256, 4, 4, 64, 512, 32000, 10000.0, 1e-5, "fp32", 1, 256, 128)
+    assert B.ded_validate_tree(cfg, [10], [len(parent)], np.pad(parent, (0, 128 - len(parent)))[None],
+                               np.pad(token, (0, 128 - len(token)))[None]) == B.DED_OK
+    # argument errors
+    lib = B.lib()
+    import ctypes as C
+    one = (C.c_int32 * 4)()
+    assert lib.ded_build_tree(1, 1, one, one, 4, 0, one, one, one, one) == B.DED_EINVAL        # no room for the root
+    assert lib.ded_build_tree(1, -1, one, one, 4, 4, one, one, one, one) == B.DED_EINVAL
+    assert lib.ded_build_tree(1, 1, one, one, 4, 4, None, one, one, one) == B.DED_EINVAL
+    bad = (C.c_int32 * 1)(5)
+    assert lib.ded_build_tree(1, 1, bad, one, 4, 4, one, one, one, one) == B.DED_EINVAL        # length above max_len
