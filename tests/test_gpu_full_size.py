@@ -113,3 +113,66 @@ def test_c3_full_model():
     a plain causal forward in the oracle."""
     wl = di.WORKLOADS["c3"]
     _full_step_check(wl.model, wl, "c3")
+
+
+def test_c3_shape_decode_loop_lossless():
+    """Multi-step decoding at the 7B width (2 layers): candidates -> ded_build_tree -> verify -> accept,
+    repeated; the committed tokens must equal plain one-token-per-step decoding through the same library
+    token for token, and the oracle's greedy choice (one causal fp64 forward over prompt + output) at
+    every position where the oracle's top-1 margin exceeds 0.05."""
+    from paper_2407_12021_amd import binding as B
+    wl = di.WORKLOADS["c3"]
+    cfg = wl.model.with_layers(2)
+    w = di.make_weights(cfg, seed=13, std=0.05, threads=16)
+    P, n_new = 96, 24
+    prompt = di.zipf_tokens(cfg.vocab, P + 1, seed=4)
+    ver = _verifier(cfg, w, max_batch=1, kv_capacity=P + n_new + 64 + 8, max_nodes=64)
+
+    def prefill():
+        for s in range(0, P, 64):
+            n = min(64, P - s)
+            ver.verify_step([s], [di.chain_tree(n)], [prompt[s:s + n]])
+            ver.accept(mode=1)
+
+    prefill()
+    ref, r, p = [], int(prompt[P]), P
+    for _ in range(n_new + 8):
+        ver.verify_step([p], [[-1]], [[r]])
+        acc, _, newp = ver.accept(mode=0)
+        r, p = acc[0][0], newp[0]
+        ref.append(r)
+    prefill()  # the plain pass left its tokens in the cache slots after the prompt: start over
+    tri = di.SyntheticTrigram(cfg.vocab, seed=0)
+    g = np.random.default_rng(6)
+    out, steps = [], 0
+    prev, r, p = int(prompt[P - 1]), int(prompt[P]), P
+    while len(out) < n_new:
+        cands = []
+        for c in range(24):
+            a, b, seq = prev, r, []
+            for _ in range(4):
+                succ, prob = tri.successors(a, b)
+                t = int(succ[g.choice(len(succ), p=prob)])
+                seq.append(t)
+                a, b = b, t
+            cands.append(seq)
+        m = int(g.integers(0, 5))
+        cands[int(g.integers(0, 24))][:m] = ref[len(out):len(out) + m]
+        rc, parent, token, _ = B.ded_build_tree(r, cands, 64)
+        assert rc == B.DED_OK
+        ver.verify_step([p], [parent], [token])
+        acc, _, newp = ver.accept(mode=0)
+        out += acc[0]
+        prev = acc[0][-2] if len(acc[0]) > 1 else r
+        r, p = acc[0][-1], newp[0]
+        steps += 1
+    ver.close()
+    assert out[:n_new] == ref[:n_new]
+    assert steps < n_new  # some drafts were accepted
+    seq = np.concatenate([prompt[:P + 1], np.array(out[:n_new - 1], dtype=prompt.dtype)])
+    logits, _, _ = oracle.prefill(cfg, w, seq)
+    a_ref, margin = oracle.argmax_margin(logits[P:])
+    sure = margin > MARGIN
+    got = np.array(out[:n_new])
+    print(f"decode loop: {steps} steps for {len(out)} tokens; oracle-sure positions {int(sure.sum())}/{n_new}")
+    assert (got[sure] == a_ref[sure]).all()
