@@ -7,7 +7,8 @@ product path never does.
 Pinned parts (see tests/test_oracle_pins.py): every function below is pinned by closed forms,
 library special cases, brute force on tiny trees or the chain == autoregressive invariant; the
 pseudo-sequence builder by the set of root-to-node paths, hand-worked cases and the equality of a
-candidate's logits in the merged tree and in its own chain.
+candidate's logits in the merged tree and in its own chain; the temperature / top-p sampler by brute
+force over subsets on tiny vocabularies, its limits (argmax, plain soft-max frequencies) and monotonicity.
 Parity unpinned: none.
 """
 from .decoder import (  # noqa: F401
@@ -16,3 +17,4 @@ from .decoder import (  # noqa: F401
 )
 from .accept import argmax_margin, accept_walk, compact_rows  # noqa: F401
 from .trie import build_trie  # noqa: F401
+from .sample import nucleus, sample_top_p, sample_rows  # noqa: F401

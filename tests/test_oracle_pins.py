@@ -464,3 +464,79 @@ def test_candidate_in_merged_tree_equals_its_own_chain(small_cfg, small_model):
             path.append(node)
             node = parent[node]
         np.testing.assert_allclose(logits[path[::-1]], ref, rtol=0, atol=1e-10)
+
+
+# ---------------------------------------------------------------------------------------------
+# Temperature / top-p sampling of the model's token (stochastic approval, Sec. 2.4 / 4.4)
+# ---------------------------------------------------------------------------------------------
+
+
+def test_nucleus_brute_force_on_tiny_vocabularies():
+    """The nucleus is the smallest set of tokens that (a) reaches top_p, (b) is closed under 'at least as
+    probable as a member' (highest-probability tokens first, ties admitted together): enumerate all subsets."""
+    import itertools
+    g = np.random.default_rng(31)
+    for trial in range(300):
+        V = int(g.integers(1, 8))
+        p = g.random(V) ** 3
+        if trial % 3 == 0 and V > 2:
+            p[int(g.integers(0, V))] = p[int(g.integers(0, V))]  # a tie
+        p /= p.sum()
+        top_p = float(g.choice([0.05, 0.3, 0.5, 0.9, 0.999, 1.0]))
+        best = None
+        for r in range(1, V + 1):
+            for S in itertools.combinations(range(V), r):
+                inS = np.zeros(V, bool)
+                inS[list(S)] = True
+                closed = all(inS[j] for i in S for j in range(V) if p[j] >= p[i])
+                if closed and p[inS].sum() >= min(top_p, p.sum()) - 1e-15 and (best is None or r < best.sum()):
+                    best = inS
+            if best is not None:
+                break
+        got = oracle.nucleus(p, min(top_p, float(np.cumsum(np.sort(p)[::-1])[-1])))
+        assert (got == best).all(), (p, top_p, got, best)
+
+
+def test_sampler_limits_and_monotonicity():
+    g = np.random.default_rng(32)
+    logits = g.normal(0, 2.0, size=50)
+    # temperature -> 0 and top_p -> 0 both give the argmax, whatever u is
+    for u in (0.0, 0.3, 0.999999):
+        assert oracle.sample_top_p(logits, 1e-3, 1.0, u)[0] == int(np.argmax(logits))
+        assert oracle.sample_top_p(logits, 1.0, 1e-9, u)[0] == int(np.argmax(logits))
+    # the token id is non-decreasing in u, and u = 0 gives the lowest id of the nucleus
+    us = np.linspace(0, 1, 400, endpoint=False)
+    toks = [oracle.sample_top_p(logits, 0.8, 0.9, float(u))[0] for u in us]
+    assert all(a <= b for a, b in zip(toks, toks[1:]))
+    p = np.exp(logits / 0.8 - (logits / 0.8).max())
+    p /= p.sum()
+    keep = oracle.nucleus(p, 0.9)
+    assert toks[0] == int(np.flatnonzero(keep)[0]) and set(toks) <= set(np.flatnonzero(keep).tolist())
+    # a stratified grid of u reproduces the renormalised nucleus probabilities to within one grid cell
+    n = 20000
+    cnt = np.bincount([oracle.sample_top_p(logits, 0.8, 0.9, (k + 0.5) / n)[0] for k in range(n)], minlength=50)
+    want = np.where(keep, p, 0) / p[keep].sum()
+    assert np.abs(cnt / n - want).max() <= 1.0 / n + 1e-12
+    # top_p = 1 keeps everything: plain soft-max sampling
+    cnt = np.bincount([oracle.sample_top_p(logits, 1.0, 1.0, (k + 0.5) / n)[0] for k in range(n)], minlength=50)
+    sm = np.exp(logits - logits.max())
+    sm /= sm.sum()
+    assert np.abs(cnt / n - sm).max() <= 1.0 / n + 1e-12
+
+
+def test_sampled_walk_reduces_to_greedy_and_uses_the_sampled_tokens():
+    """Stochastic approval = the same walk fed with sampled tokens: with a vanishing temperature it is the
+    greedy walk; otherwise the path follows exactly the children that equal the sampled token."""
+    g = np.random.default_rng(33)
+    parent = np.array([-1, 0, 0, 1, 1, 2])
+    token = np.array([5, 1, 2, 3, 4, 3])
+    logits = g.normal(0, 1, size=(6, 8))
+    greedy, _ = oracle.argmax_margin(logits)
+    cold, _ = oracle.sample_rows(logits, 1e-4, 1.0, g.random(6))
+    assert (cold == greedy).all()
+    for trial in range(50):
+        model, _ = oracle.sample_rows(logits, 1.5, 0.95, g.random(6))
+        acc, path = oracle.accept_walk(parent, token, model)
+        for a, b in zip(path, path[1:]):
+            assert parent[b] == a and token[b] == model[a]
+        assert acc[-1] == model[path[-1]] and not any(parent[c] == path[-1] and token[c] == model[path[-1]] for c in range(6))
