@@ -348,6 +348,23 @@ def main():
 
     decode = decode_loop_bench(di, ver, wl, prefix, int(token[0]))
 
+    # stochastic approval (temperature 0.8, top-p 0.9): the extra cost of sampling the model's token at 64 nodes
+    g = np.random.default_rng(3)
+    ver.profile(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_st = 10
+    for i in range(n_st):
+        ver.verify_step([P], [parent], [planted[i % len(planted)]])
+        ver.sample(0.8, 0.9, [g.random(len(parent)).astype(np.float32)])
+        ver.accept(mode=0)
+    torch.cuda.synchronize()
+    dt_st = time.perf_counter() - t0
+    prof_st = ver.profile_read()
+    ver.profile(False)
+    stochastic = {"temperature": 0.8, "top_p": 0.9, "ms_per_step_with_event_brackets": dt_st / n_st * 1e3,
+                  "sample_kernel_us": prof_st["sample_top_p"][0] / max(prof_st["sample_top_p"][1], 1) * 1e3}
+
     # per-kernel-class times (separate pass: event brackets add overhead)
     ver.profile(True)
     prof_steps = 5
@@ -396,6 +413,7 @@ def main():
         "raw_trigram_tree": {"steps_per_s": raw_steps / dt_raw, "verified_tokens_per_s": n_tok_raw / dt_raw,
                              "mean_accepted_per_step": n_tok_raw / raw_steps},
         "decode_loop": decode,
+        "stochastic_approval": stochastic,
         "kernel_ms_per_step": kernels_ms,
         "roofline": {"bound": "hbm",
                      "kernel": "gate/up projection GEMM with SiLU*up epilogue (gemm_wide_kernel, 3 feature groups per "

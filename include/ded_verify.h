@@ -142,6 +142,19 @@ void ded_verify_free(ded_ctx *ctx);
 int ded_verify_step(ded_ctx *ctx, int32_t batch, const int32_t *prefix_len, const int32_t *n_nodes,
                     const int32_t *parent, const int32_t *token, float *logits_out);
 
+/* Stochastic approval (Sec. 2.4: at each position a token is sampled from the model's distribution and
+ * compared with the draft token; Sec. 4.4 varies temperature and top-p).  Optional call between
+ * ded_verify_step and ded_accept: replaces the model's token at every node of the pending step - the
+ * argmax - by a sample; ded_accept then walks with the sampled tokens.
+ *   p_i = softmax(logits / temperature); the nucleus is the smallest set of most probable tokens whose
+ *   probabilities reach top_p (ties with its last member included); the token is the smallest id j of
+ *   the nucleus with  sum_{i in nucleus, i <= j} p_i > u * sum_{nucleus} p.
+ *   temperature > 0, 0 < top_p <= 1
+ *   uniform  host [batch][max_nodes], one number in [0, 1) per node, drawn by the caller
+ * Synchronises the stream.  ded_get_argmax afterwards returns the sampled tokens (margins unchanged).
+ * Errors: DED_EINVAL (range of an argument, null), DED_ESTATE (no pending step), DED_EHIP. */
+int ded_sample(ded_ctx *ctx, float temperature, float top_p, const float *uniform);
+
 /* Approval walk + cache compaction for the pending step (Sec. 2.4: a draft token is approved when
  * it equals the model's token at its parent; the draft is discarded from the first mismatch on).
  *   mode 0  greedy walk: end node = the deepest approved node (lowest index among equally deep);

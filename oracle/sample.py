@@ -31,7 +31,8 @@ def nucleus(p: np.ndarray, top_p: float) -> np.ndarray:
 
 def sample_top_p(logits: np.ndarray, temperature: float, top_p: float, u: float):
     """One row.  Returns (token, info): info holds the two distances that say how close the decision was to
-    flipping: 'nucleus_slack' = smallest |cumulative probability - top_p| around the nucleus boundary,
+    flipping: 'nucleus_slack' = how far top_p is from admitting one token fewer or needing one more
+    ('edge_mass' = the probability that would then enter or leave the nucleus),
     'cdf_slack' = distance of u from the nearest CDF step (both as probabilities)."""
     x = np.asarray(logits, dtype=np.float64) / float(temperature)
     e = np.exp(x - x.max())
@@ -43,10 +44,15 @@ def sample_top_p(logits: np.ndarray, temperature: float, top_p: float, u: float)
     j = int(np.searchsorted(cdf, u * total, side="right"))  # first j with cdf[j] > u * total
     j = min(j, len(ids) - 1)
     steps = np.concatenate([[0.0], cdf]) / total
+    # how far top_p is from admitting one token fewer / needing one token more
     order = np.argsort(-p, kind="stable")
     cum = np.cumsum(p[order])
+    k = min(int(np.searchsorted(cum, top_p, side="left")), len(p) - 1)
+    fewer = top_p - cum[k - 1] if k > 0 else np.inf
+    more = cum[k] - top_p if k < len(p) - 1 else np.inf
+    edge = p[order[k]] + (p[order[k + 1]] if k + 1 < len(p) else 0.0)  # mass that a flipped boundary would move
     info = {"nucleus_size": int(keep.sum()), "cdf_slack": float(np.abs(steps - u).min()),
-            "nucleus_slack": float(np.abs(cum - top_p).min())}
+            "nucleus_slack": float(min(fewer, more)), "edge_mass": float(edge)}
     return int(ids[j]), info
 
 

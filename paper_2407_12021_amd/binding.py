@@ -21,7 +21,7 @@ DED_F32, DED_BF16 = 0, 1
 
 EXPORTS = [
     "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_build_tree", "ded_verify_init", "ded_verify_free",
-    "ded_verify_step", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
+    "ded_verify_step", "ded_sample", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
     "ded_profile_enable", "ded_profile_read", "ded_strerror",
 ]
 
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.ded_kv_layer_bytes.argtypes = [C.POINTER(ded_config)]
         L.ded_validate_tree.restype = C.c_int
         L.ded_validate_tree.argtypes = [C.POINTER(ded_config), C.c_int32, i32p, i32p, i32p, i32p]
+        L.ded_sample.restype = C.c_int
+        L.ded_sample.argtypes = [vp, C.c_float, C.c_float, C.POINTER(C.c_float)]
         L.ded_build_tree.restype = C.c_int
         L.ded_build_tree.argtypes = [C.c_int32, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
         L.ded_verify_init.restype = C.c_int
@@ -330,6 +332,16 @@ class Verifier:
             raise DedError(rc, "ded_verify_step")
         self._batch = B
         return logits
+
+    def sample(self, temperature: float, top_p: float, uniform):
+        """uniform: one sequence of floats in [0, 1) per batch entry (one per node)."""
+        u = np.zeros((self._batch, self.max_nodes), np.float32)
+        for b, r in enumerate(uniform):
+            u[b, : len(r)] = np.asarray(r, dtype=np.float32)
+        rc = int(lib().ded_sample(self.ctx, float(temperature), float(top_p),
+                                  u.ctypes.data_as(C.POINTER(C.c_float))))
+        if rc != DED_OK:
+            raise DedError(rc, "ded_sample")
 
     def accept(self, mode=0):
         rc, acc, nacc, path, newp = ded_accept(self.ctx, mode, self._batch, self.max_nodes)

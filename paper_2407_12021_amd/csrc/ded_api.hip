@@ -24,12 +24,12 @@ inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 enum KClass {
   KC_META = 0, KC_ROPE_TABLE, KC_EMBED, KC_RMSNORM, KC_GEMM_QKV, KC_QKV_EPILOGUE, KC_TREE_ATTN, KC_ATTN_MERGE,
   KC_GEMM_O, KC_GEMM_GATE_UP, KC_SILU_MUL, KC_GEMM_DOWN, KC_GEMM_LM_HEAD, KC_ARGMAX, KC_EXPORT, KC_WALK,
-  KC_COMPACT, KC_LAYOUT, KC_COUNT
+  KC_COMPACT, KC_LAYOUT, KC_SAMPLE, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "meta_upload", "rope_table", "embed", "add_rmsnorm", "gemm_qkv", "qkv_rope_epilogue", "tree_attention",
     "attention_merge", "gemm_o", "gemm_gate_up", "silu_mul", "gemm_down", "gemm_lm_head", "argmax",
-    "export_logits", "accept_walk", "kv_compact", "layout_convert"};
+    "export_logits", "accept_walk", "kv_compact", "layout_convert", "sample_top_p"};
 
 struct Carve {  // bump allocator over the workspace (base may be null when only sizing)
   char* base;
@@ -90,6 +90,7 @@ struct ded_ctx {
   // results
   int32_t* d_amax = nullptr;
   float* d_margin = nullptr;
+  float* d_uniform = nullptr;  // [rows] uniform numbers of ded_sample
   int32_t *d_nacc = nullptr, *d_path = nullptr, *d_acctok = nullptr;
   char* h_res = nullptr;  // pinned: amax | margin | nacc | path | acctok
   size_t res_bytes = 0;
@@ -280,6 +281,7 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
   int stride = c.max_nodes + 1;
   int32_t* amax = w.take<int32_t>(z.max_rows_pad);
   float* margin = w.take<float>(z.max_rows_pad);
+  float* uniform = w.take<float>(z.max_rows_pad);
   int32_t* nacc = w.take<int32_t>(c.max_batch);
   int32_t* path = w.take<int32_t>((int64_t)c.max_batch * stride);
   int32_t* acct = w.take<int32_t>((int64_t)c.max_batch * stride);
@@ -295,6 +297,7 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
     ctx->off_n = o_n;
     ctx->d_amax = amax;
     ctx->d_margin = margin;
+    ctx->d_uniform = uniform;
     ctx->d_nacc = nacc;
     ctx->d_path = path;
     ctx->d_acctok = acct;
@@ -775,6 +778,26 @@ int ded_accept(ded_ctx* c, int32_t mode, int32_t* accepted_tokens, int32_t* n_ac
     memcpy(compaction_idx + (size_t)b * stride, h_path + (size_t)b * stride, sizeof(int32_t) * len);
   }
   c->pending = false;
+  return DED_OK;
+}
+
+int ded_sample(ded_ctx* c, float temperature, float top_p, const float* uniform) {
+  if (!c || !uniform) return DED_EINVAL;
+  if (!(temperature > 0.f) || !(top_p > 0.f) || !(top_p <= 1.f)) return DED_EINVAL;
+  if (!c->pending || !c->have_argmax) return DED_ESTATE;
+  const int mn = c->cfg.max_nodes, rows = c->batch * c->n_step;
+  float* h_u = reinterpret_cast<float*>(c->h_res);  // nothing else is in flight on the pinned result block
+  for (int b = 0; b < c->batch; ++b)
+    for (int i = 0; i < c->n_step; ++i) {
+      float u = i < c->s_n[b] ? uniform[(size_t)b * mn + i] : 0.f;
+      if (!(u >= 0.f) || !(u < 1.f)) return DED_EINVAL;
+      h_u[b * c->n_step + i] = u;
+    }
+  HIP_TRY(hipMemcpyAsync(c->d_uniform, h_u, sizeof(float) * rows, hipMemcpyHostToDevice, c->stream));
+  { ProfScope p(c, KC_SAMPLE);
+    launch_sample_top_p(c->logits, c->md.V, rows, c->md.V, temperature, top_p, c->d_uniform, c->d_amax, c->stream); }
+  if (launch_status() != DED_OK) return DED_EHIP;
+  HIP_TRY(hipStreamSynchronize(c->stream));  // h_res is free again
   return DED_OK;
 }
 

@@ -31,6 +31,9 @@ void launch_rope_table(float2* tab, const int32_t* pos, int rows, int hd, float 
 // Per-row argmax (lowest index on exact ties) and top-1 minus top-2 over V fp32 logits.
 void launch_argmax(const float* logits, int64_t row_stride, int rows, int V, int32_t* amax,
                    float* margin, hipStream_t s);
+// Per-row temperature / top-p sample (inverse CDF of uniform[r] over the nucleus in id order) -> token_out[r].
+void launch_sample_top_p(const float* logits, int64_t row_stride, int rows, int V, float temperature, float top_p,
+                         const float* uniform, int32_t* token_out, hipStream_t s);
 // Copy rows of real nodes to the caller's [batch][max_nodes][V] logits buffer.
 void launch_export_logits(float* dst, const float* src, int64_t src_stride, const StepMeta& m,
                           int max_nodes, int V, hipStream_t s);

@@ -97,6 +97,260 @@ void launch_argmax(const float* logits, int64_t row_stride, int rows, int V, int
 }
 
 // ------------------------------------------------------------------------------------------
+// Temperature / top-p sampling of the model's token at every node (stochastic approval, Sec. 2.4: a token
+// is sampled from the model's distribution and compared with the draft; Sec. 4.4 varies temperature and
+// top-p).  One workgroup per row.  p_i = softmax(logits / T); the nucleus is the smallest set of most
+// probable tokens reaching top_p, ties with its last member included; the token is the inverse CDF of the
+// caller's uniform number over the nucleus in token-id order.
+// p is monotone in the logit, so the nucleus is {logit >= t*} with t* the largest threshold under which the
+// set still reaches top_p: found by bisection over the order-preserving integer image of fp32 (<= 32
+// passes over the row, which stays in L2).  Sums are formed in a fixed order (per thread, wavefront
+// shuffles, wavefront order), so the result is reproducible.
+constexpr int SAMPLE_THREADS = 1024;
+
+__device__ inline uint32_t ordered_key(float v) {
+  const uint32_t b = __float_as_uint(v);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ inline float block_sum(float v, float* sh) {
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = 0.f;
+  for (int w = 0; w < SAMPLE_THREADS / 64; ++w) r += sh[w];
+  return r;
+}
+
+// exclusive prefix of v over the threads of the block and the block total, in a fixed order (wavefront scan by
+// shuffles, then the wavefront totals one after the other)
+__device__ inline float block_exclusive_scan(float v, float* sh_w, float& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float inc = v;
+  for (int off = 1; off < 64; off <<= 1) {
+    const float o = __shfl_up(inc, off);
+    if (lane >= off) inc += o;
+  }
+  __syncthreads();
+  if (lane == 63) sh_w[wave] = inc;
+  __syncthreads();
+  float before = 0.f, all = 0.f;
+  for (int w = 0; w < SAMPLE_THREADS / 64; ++w) {
+    if (w < wave) before += sh_w[w];
+    all += sh_w[w];
+  }
+  total = all;
+  return before + (inc - v);
+}
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_top_p_kernel(const float* __restrict__ logits,
+                                                                      int64_t row_stride, int V, float inv_temp,
+                                                                      float top_p, const float* __restrict__ uniform,
+                                                                      int32_t* __restrict__ token_out) {
+  __shared__ float sh[SAMPLE_THREADS / 64];
+  __shared__ uint32_t sh_k[2 * (SAMPLE_THREADS / 64)];
+  __shared__ int sh_pick, sh_last;
+  const float* row = logits + (int64_t)blockIdx.x * row_stride;
+  const int tid = threadIdx.x;
+  // pass 1: extreme keys
+  uint32_t kmax = 0u, kmin = 0xffffffffu;
+  for (int i = tid; i < V; i += SAMPLE_THREADS) {
+    const uint32_t k = ordered_key(row[i]);
+    kmax = k > kmax ? k : kmax;
+    kmin = k < kmin ? k : kmin;
+  }
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint32_t a = __shfl_xor(kmax, off), b = __shfl_xor(kmin, off);
+    kmax = a > kmax ? a : kmax;
+    kmin = b < kmin ? b : kmin;
+  }
+  if ((tid & 63) == 0) {
+    sh_k[tid >> 6] = kmax;
+    sh_k[SAMPLE_THREADS / 64 + (tid >> 6)] = kmin;
+  }
+  __syncthreads();
+  for (int w = 0; w < SAMPLE_THREADS / 64; ++w) {
+    kmax = sh_k[w] > kmax ? sh_k[w] : kmax;
+    kmin = sh_k[SAMPLE_THREADS / 64 + w] < kmin ? sh_k[SAMPLE_THREADS / 64 + w] : kmin;
+  }
+  const uint32_t bmax = (kmax & 0x80000000u) ? (kmax & 0x7fffffffu) : ~kmax;
+  const float m = __uint_as_float(bmax);  // row maximum
+  // weight of the tokens whose key is >= t  (t = 0: all)
+  auto mass = [&](uint32_t t) {
+    float s = 0.f;
+    for (int i = tid; i < V; i += SAMPLE_THREADS) {
+      const float l = row[i];
+      if (ordered_key(l) >= t) s += __expf((l - m) * inv_temp);
+    }
+    return block_sum(s, sh);
+  };
+  const float Z = mass(0u);
+  const float need = top_p * Z;
+  // largest t with mass(t) >= need:  mass(lo) >= need holds (lo = smallest key), mass(hi) < need (hi beyond the largest)
+  uint32_t lo = kmin, hi = kmax + 1u;  // logits are finite, so kmax + 1 does not wrap
+  while (hi - lo > 1u) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    if (mass(mid) >= need) lo = mid;
+    else hi = mid;
+  }
+  // inverse CDF over the nucleus in id order: thread t owns the ids [t * chunk, (t + 1) * chunk)
+  const int chunk = (V + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
+  const int i0 = tid * chunk, i1 = min(V, i0 + chunk);
+  float own = 0.f;
+  int last_kept = -1;
+  for (int i = i0; i < i1; ++i) {
+    const float l = row[i];
+    if (ordered_key(l) >= lo) {
+      own += __expf((l - m) * inv_temp);
+      last_kept = i;
+    }
+  }
+  if (tid == 0) {
+    sh_pick = 0x7fffffff;
+    sh_last = -1;
+  }
+  float total;
+  const float before = block_exclusive_scan(own, sh, total);  // its barriers also publish sh_pick / sh_last
+  if (last_kept >= 0) atomicMax(&sh_last, last_kept);
+  const float target = uniform[blockIdx.x] * total;
+  if (own > 0.f && before <= target) {
+    float run = before;
+    for (int i = i0; i < i1; ++i) {
+      const float l = row[i];
+      if (ordered_key(l) >= lo) {
+        run += __expf((l - m) * inv_temp);
+        if (run > target) {
+          atomicMin(&sh_pick, i);
+          break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // if rounding left the target at or above the total nobody picked: take the last id of the nucleus
+  if (tid == 0) token_out[blockIdx.x] = sh_pick != 0x7fffffff ? sh_pick : sh_last;
+}
+
+// Same sampler for vocabularies that fit LDS: the weights exp((l - max) / T) are computed once and kept in LDS
+// (they are monotone in the logit, so the bisection runs on their bit patterns), which turns the ~34 passes
+// over the row into LDS traffic.
+constexpr int SAMPLE_LDS_V = 36864;  // 144 KiB of weights
+
+__global__ __launch_bounds__(SAMPLE_THREADS) void sample_top_p_lds_kernel(const float* __restrict__ logits,
+                                                                          int64_t row_stride, int V, float inv_temp,
+                                                                          float top_p, const float* __restrict__ uniform,
+                                                                          int32_t* __restrict__ token_out) {
+  __shared__ float e[SAMPLE_LDS_V];
+  __shared__ float sh[SAMPLE_THREADS / 64];
+  __shared__ int sh_pick, sh_last;
+  const float* row = logits + (int64_t)blockIdx.x * row_stride;
+  const int tid = threadIdx.x;
+  float m = -INFINITY;
+  for (int i = tid; i < V; i += SAMPLE_THREADS) m = fmaxf(m, row[i]);
+  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((tid & 63) == 0) sh[tid >> 6] = m;
+  __syncthreads();
+  for (int w = 0; w < SAMPLE_THREADS / 64; ++w) m = fmaxf(m, sh[w]);
+  float z = 0.f;
+  uint32_t kmin = 0xffffffffu;
+  for (int i = tid; i < V; i += SAMPLE_THREADS) {
+    const float w = __expf((row[i] - m) * inv_temp);  // in [0, 1]: its bit pattern orders like its value
+    e[i] = w;
+    z += w;
+    kmin = min(kmin, __float_as_uint(w));
+  }
+  const float Z = block_sum(z, sh);
+  for (int off = 32; off >= 1; off >>= 1) kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
+  __shared__ uint32_t sh_k[SAMPLE_THREADS / 64];
+  if ((tid & 63) == 0) sh_k[tid >> 6] = kmin;
+  __syncthreads();
+  for (int w = 0; w < SAMPLE_THREADS / 64; ++w) kmin = min(kmin, sh_k[w]);
+  // largest t with mass(t) >= need, mass(t) = weight of {bits(w) >= t}: 8-way search, seven thresholds per pass
+  // over the LDS copy (one block reduction per pass instead of three)
+  __shared__ float sh7[7][SAMPLE_THREADS / 64];
+  const float need = top_p * Z;
+  uint32_t lo = kmin, hi = 0x3f800000u + 1u;  // mass(lo) >= need; the largest weight is exp(0) = 1, so mass(hi) = 0
+  while (hi - lo > 1u) {
+    const uint32_t span = hi - lo;
+    uint32_t t[7];
+#pragma unroll
+    for (int j = 0; j < 7; ++j) t[j] = lo + (uint32_t)(((uint64_t)span * (j + 1)) >> 3);  // lo <= t[j] < hi, non-decreasing
+    float sj[7] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int i = tid; i < V; i += SAMPLE_THREADS) {
+      const float w = e[i];
+      const uint32_t k = __float_as_uint(w);
+#pragma unroll
+      for (int j = 0; j < 7; ++j) sj[j] += k >= t[j] ? w : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 7; ++j)
+      for (int off = 32; off >= 1; off >>= 1) sj[j] += __shfl_xor(sj[j], off);
+    __syncthreads();
+    if ((tid & 63) == 0) {
+#pragma unroll
+      for (int j = 0; j < 7; ++j) sh7[j][tid >> 6] = sj[j];
+    }
+    __syncthreads();
+    uint32_t nlo = lo, nhi = hi;
+#pragma unroll
+    for (int j = 0; j < 7; ++j) {
+      float f = 0.f;
+      for (int w = 0; w < SAMPLE_THREADS / 64; ++w) f += sh7[j][w];
+      if (f >= need) nlo = t[j] > nlo ? t[j] : nlo;         // thresholds that still reach the target move lo up
+      else nhi = t[j] < nhi ? t[j] : nhi;                    // the first that does not becomes hi
+    }
+    if (nlo == lo && nhi == hi) break;  // cannot happen while span > 1 (t[6] > lo or t[0] == lo handled), safety only
+    lo = nlo;
+    hi = nhi;
+  }
+  const int chunk = (V + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
+  const int i0 = tid * chunk, i1 = min(V, i0 + chunk);
+  float own = 0.f;
+  int last_kept = -1;
+  for (int i = i0; i < i1; ++i) {
+    const float w = e[i];
+    if (__float_as_uint(w) >= lo) {
+      own += w;
+      last_kept = i;
+    }
+  }
+  if (tid == 0) {
+    sh_pick = 0x7fffffff;
+    sh_last = -1;
+  }
+  float total;
+  const float before = block_exclusive_scan(own, sh, total);  // its barriers also publish sh_pick / sh_last
+  if (last_kept >= 0) atomicMax(&sh_last, last_kept);
+  const float target = uniform[blockIdx.x] * total;
+  if (own > 0.f && before <= target) {
+    float run = before;
+    for (int i = i0; i < i1; ++i) {
+      const float w = e[i];
+      if (__float_as_uint(w) >= lo) {
+        run += w;
+        if (run > target) {
+          atomicMin(&sh_pick, i);
+          break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) token_out[blockIdx.x] = sh_pick != 0x7fffffff ? sh_pick : sh_last;
+}
+
+void launch_sample_top_p(const float* logits, int64_t row_stride, int rows, int V, float temperature, float top_p,
+                         const float* uniform, int32_t* token_out, hipStream_t s) {
+  if (rows <= 0) return;
+  if (V <= SAMPLE_LDS_V)
+    hipLaunchKernelGGL(sample_top_p_lds_kernel, dim3(rows), dim3(SAMPLE_THREADS), 0, s, logits, row_stride, V,
+                       1.0f / temperature, top_p, uniform, token_out);
+  else
+    hipLaunchKernelGGL(sample_top_p_kernel, dim3(rows), dim3(SAMPLE_THREADS), 0, s, logits, row_stride, V,
+                       1.0f / temperature, top_p, uniform, token_out);
+}
+
+// ------------------------------------------------------------------------------------------
 __global__ void export_logits_kernel(float* __restrict__ dst, const float* __restrict__ src,
                                      int64_t src_stride, const int32_t* __restrict__ seq_n, int n_step,
                                      int max_nodes, int V) {

@@ -145,3 +145,10 @@ def test_build_tree_paper_shape_and_validation():
     assert lib.ded_build_tree(1, 1, one, one, 4, 4, None, one, one, one) == B.DED_EINVAL
     bad = (C.c_int32 * 1)(5)
     assert lib.ded_build_tree(1, 1, bad, one, 4, 4, one, one, one, one) == B.DED_EINVAL        # length above max_len
+
+
+def test_sample_rejects_null_context():
+    import ctypes as C
+    from paper_2407_12021_amd import binding as B
+    u = (C.c_float * 4)()
+    assert B.lib().ded_sample(None, 1.0, 0.9, u) == B.DED_EINVAL

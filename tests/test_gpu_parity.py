@@ -232,3 +232,86 @@ def test_zero_layer_bf16_gemm_path():
         assert np.abs(logits[b, :n] - ref).max() <= 2e-2 * max(1.0, np.abs(ref).max() / 4)
         assert (a_gpu[b, :n] == np.argmax(logits[b, :n], axis=1)).all()
     ver.close()
+
+
+SAMPLE_SLACK = 1e-4  # fp32 sums of up to 32000 weights against fp64: decisions closer than this to a boundary may flip
+
+
+def _check_sampling(ver, logits_gpu, parents, tokens, combos, seed):
+    """ded_sample against the oracle's sampler fed with the GPU's own fp32 logits (the decision is taken in the
+    kernel's precision on both sides; logits parity is checked elsewhere).  Every decision is checked: the token
+    must equal the oracle's when u is clear of every CDF step by SAMPLE_SLACK (counted as `exact`), and in any
+    case u must lie inside the token's own CDF interval widened by SAMPLE_SLACK (with a 32000-token vocabulary
+    the steps are ~3e-5 apart, so most decisions are of this second kind)."""
+    g = np.random.default_rng(seed)
+    exact = loose = 0
+    for temperature, top_p in combos:
+        us = [g.random(len(p)).astype(np.float32) for p in parents]
+        ver.sample(temperature, top_p, us)
+        a_gpu, _ = ver.get_argmax()
+        for b, parent in enumerate(parents):
+            n = len(parent)
+            lg = logits_gpu[b, :n].astype(np.float64)
+            ref, info = oracle.sample_rows(lg, temperature, top_p, us[b].astype(np.float64))
+            for i in range(n):
+                tok, u = int(a_gpu[b, i]), float(us[b][i])
+                edge = info[i]["edge_mass"] if info[i]["nucleus_slack"] <= SAMPLE_SLACK else 0.0
+                if info[i]["cdf_slack"] > SAMPLE_SLACK + edge:
+                    assert tok == ref[i], (temperature, top_p, b, i)
+                    exact += 1
+                    continue
+                x = lg[i] / temperature
+                p = np.exp(x - x.max())
+                p /= p.sum()
+                keep = oracle.nucleus(p, top_p)
+                if edge == 0.0:
+                    assert keep[tok], (temperature, top_p, b, i)
+                keep[tok] = True
+                ids = np.flatnonzero(keep)
+                cdf = np.cumsum(p[ids]) / p[ids].sum()
+                pos = int(np.searchsorted(ids, tok))
+                lo = cdf[pos - 1] if pos else 0.0
+                assert lo - SAMPLE_SLACK - edge <= u <= cdf[pos] + SAMPLE_SLACK + edge, (temperature, top_p, b, i)
+                loose += 1
+    return exact, loose, a_gpu
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_stochastic_approval(dtype):
+    """Temperature / top-p sampling of the model's token and the walk that uses it."""
+    if dtype == "fp32":
+        cfg = di.ModelConfig("samp-f32", 2, 64, 4, 2, 16, 96, 500, dtype="fp32")
+    else:
+        cfg = di.ModelConfig("samp-bf16", 1, 256, 2, 2, 128, 128, 32000, dtype="bf16")  # full-size vocabulary
+    w = di.make_weights(cfg, seed=5, gain_jitter=0.1, std=0.3 if dtype == "fp32" else 0.08)
+    ver = _verifier(cfg, w, max_batch=2, kv_capacity=128, max_nodes=40)
+    prefixes = [di.zipf_tokens(cfg.vocab, 21, seed=7), di.zipf_tokens(cfg.vocab, 9, seed=8)]
+    ver.verify_step([0, 0], [di.chain_tree(21), di.chain_tree(9)], prefixes)
+    ver.accept(mode=1)
+    parents = [di.random_tree(40, None, seed=1), di.random_tree(13, None, seed=2)]
+    tokens = [di.zipf_tokens(cfg.vocab, 40, seed=3), di.zipf_tokens(cfg.vocab, 13, seed=4)]
+    logits = ver.verify_step([21, 9], parents, tokens, want_logits=True).cpu().numpy()
+    greedy, _ = ver.get_argmax()
+    combos = [(1.0, 1.0), (0.7, 0.9), (1.5, 0.5), (1.0, 0.05), (0.3, 0.99), (2.0, 0.8)]
+    exact, loose, last = _check_sampling(ver, logits, parents, tokens, combos, seed=9)
+    print(f"sampling [{dtype}]: {exact} decisions equal to the oracle's, {loose} more within {SAMPLE_SLACK} of a CDF step "
+          f"and inside their own CDF interval")
+    assert exact >= (0.9 if dtype == "fp32" else 0.2) * (exact + loose)
+    # the walk uses the sampled tokens
+    acc, path, newp = ver.accept(mode=0)
+    for b, (parent, token) in enumerate(zip(parents, tokens)):
+        acc2, path2 = oracle.accept_walk(parent, token, last[b, :len(parent)])
+        assert acc[b] == acc2 and path[b] == path2
+    # a vanishing temperature is greedy decoding; errors
+    ver.verify_step([21, 9], parents, tokens)
+    ver.sample(1e-3, 1.0, [np.full(40, 0.5, np.float32), np.full(13, 0.999, np.float32)])
+    cold, _ = ver.get_argmax()
+    assert (cold == greedy).all()
+    from paper_2407_12021_amd.binding import DedError
+    for bad in ((0.0, 0.9, 0.5), (1.0, 0.0, 0.5), (1.0, 1.5, 0.5), (1.0, 0.9, 1.0), (1.0, 0.9, -0.1)):
+        with pytest.raises(DedError):
+            ver.sample(bad[0], bad[1], [np.full(40, bad[2], np.float32), np.full(13, 0.5, np.float32)])
+    ver.accept(mode=0)
+    with pytest.raises(DedError):  # no pending step
+        ver.sample(1.0, 0.9, [np.full(40, 0.5, np.float32), np.full(13, 0.5, np.float32)])
+    ver.close()
