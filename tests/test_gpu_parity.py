@@ -315,3 +315,20 @@ def test_stochastic_approval(dtype):
     with pytest.raises(DedError):  # no pending step
         ver.sample(1.0, 0.9, [np.full(40, 0.5, np.float32), np.full(13, 0.5, np.float32)])
     ver.close()
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_maximum_tree_size_and_full_cache(dtype):
+    """256 nodes (all four ancestor-mask words), once as a random tree and once as one 256-deep chain, with the
+    cache filled to its last slot (prefix_len + n_nodes == kv_capacity)."""
+    hd = 128 if dtype == "bf16" else 32
+    cfg = di.ModelConfig("max-" + dtype, 1, 128, 2, 1, hd, 128, 192, dtype=dtype)
+    w = di.make_weights(cfg, seed=8, gain_jitter=0.1)
+    prefix = di.zipf_tokens(cfg.vocab, 64, seed=3)
+    _, pk, pv = oracle.prefill(cfg, w, prefix)
+    for parent in (di.random_tree(256, None, seed=5), di.chain_tree(256)):
+        ver = _verifier(cfg, w, max_batch=1, kv_capacity=64 + 256, max_nodes=256)
+        gpu_prefill(ver, [prefix], chunk=64)
+        token = di.zipf_tokens(cfg.vocab, 256, seed=6)
+        check_step(cfg, w, ver, prefix, parent, token, pk, pv)
+        ver.close()
