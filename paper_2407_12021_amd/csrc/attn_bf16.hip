@@ -33,8 +33,20 @@ __device__ unsigned long long* g_atrace = nullptr;  // [workgroup][4] wall-clock
 #define DED_ASTAMP(i)                                                                                         \
   if (g_atrace && threadIdx.x == 0)                                                                           \
     g_atrace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (i)] = wall_clock64();
+__device__ unsigned long long* g_aphase = nullptr;  // [workgroup][4] accumulated phase times of wave 0
+#define DED_APHASE_DECL unsigned long long ph_t = 0, ph_acc[4] = {0, 0, 0, 0};
+#define DED_APHASE_START ph_t = wall_clock64();
+#define DED_APHASE(i) { unsigned long long now_ = wall_clock64(); ph_acc[i] += now_ - ph_t; ph_t = now_; }
+#define DED_APHASE_FLUSH                                                                                      \
+  if (g_aphase && threadIdx.x == 0)                                                                           \
+    for (int i_ = 0; i_ < 4; ++i_)                                                                            \
+      g_aphase[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + i_] = ph_acc[i_];
 #else
 #define DED_ASTAMP(i)
+#define DED_APHASE_DECL
+#define DED_APHASE_START
+#define DED_APHASE(i)
+#define DED_APHASE_FLUSH
 #endif
 
 __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
@@ -118,7 +130,9 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     d[TILE_U4 + 768] = st.v3;
   };
 
+  DED_APHASE_DECL
   auto compute_tile = [&](int buf, int t) {
+    DED_APHASE_START
     const uint4* lk = lds[buf];
     const uint4* lv = lds[buf] + TILE_U4;
     // S^T: s[kb][c][i] = score of key  t*64 + kb*32 + quad*8 + c*4 + i  against this lane's row
@@ -137,6 +151,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
         }
         s[kb][c] = acc + acc_lo;
       }
+    DED_APHASE(0)
     const int key0 = t * TILE;
     float p[2][8];
     float mx = NEG_BIG;
@@ -181,6 +196,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
     }
     l_run = l_run * alpha + lsum;
     m_run = m_new;
+    DED_APHASE(1)
     if (__any(alpha != 1.0f)) {
 #pragma unroll
       for (int hb = 0; hb < 8; ++hb) o[hb] *= alpha;
@@ -192,6 +208,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
         f16x8_t a = __builtin_bit_cast(f16x8_t, lv[((kb * 8 + hb) << 6) + lane]);
         o[hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[kb], o[hb], 0, 0, 0);
       }
+    DED_APHASE(2)
   };
 
   DED_ASTAMP(0)
@@ -212,6 +229,7 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   }
 
   DED_ASTAMP(2)
+  DED_APHASE_FLUSH
   if (active) {
     float l = l_run;
     l += __shfl_xor(l, 16);
