@@ -114,7 +114,7 @@ struct GemmEpilogue {
 // Returns false (nothing launched) on an unsupported shape.
 struct GemmPlan {
   int nwn;     // 0: stream kernel (one feature group per workgroup); 2..4: wide kernel, groups per workgroup;
-               // 8: large-row kernel (8 wavefronts: feature groups x row groups per workgroup)
+               // 8, 9: large-row kernel (256 features x 128 / 256 rows per workgroup)
   int nw;      // stream kernel: wavefronts splitting the k range
   int splits;  // split-K slices
 };

@@ -651,10 +651,12 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
 // Large-row kernel (rows_pad >= 256: batched trees).  With hundreds of rows per weight the projection is
 // bound by the matrix cores, not by the weight stream, so this is an ordinary tiled GEMM on the same
 // fragment layouts: a workgroup of 8 wavefronts owns FGS feature groups x RGS row groups (FGS * RGS == 8;
-// 4 x 2 = 256 features x 128 rows), wavefront (fg, rg) the 64 x 64 tile the other kernels also give a
-// wavefront, so the split-K hand-over and the epilogues are shared.  A stage holds CH k steps of the
-// workgroup's weights and activations in LDS (double buffered, one barrier per stage; global loads run two
-// stages ahead in registers); every weight fragment read from LDS feeds 4 matrix instructions per plane.
+// a wavefront owns GPW = 2 feature groups x 1 row group: 256 features x 256 rows per workgroup), in units of
+// the 64 x 64 tile the other kernels give a wavefront, so the split-K hand-over and the epilogues are shared.
+// A stage holds CH k steps of the workgroup's weights and activations in LDS (double buffered, one barrier
+// per stage; global loads run two stages ahead in registers).  Per k step a wavefront reads 8 weight and
+// 4 x PLANES activation fragments from LDS for 32 x PLANES matrix instructions: LDS read bandwidth, the
+// limit of a smaller wavefront tile (64 x 64: 52 % of the f16 peak), is a third lower per instruction.
 // ------------------------------------------------------------------------------------------
 __device__ inline float ssq_direct(const GemmEpilogue& e, int rb0, int lane) {
   if (!e.ssq_in) return 1.f;
@@ -665,16 +667,21 @@ __device__ inline float ssq_direct(const GemmEpilogue& e, int rb0, int lane) {
   return 1.0f / sqrtf(s * e.inv_k + e.eps);
 }
 
-constexpr int LARGE_FGS = 4, LARGE_RGS = 2, LARGE_CH = 2;
+// Two shapes (plan.nwn 8 and 9): GPW = 1 feature group per wavefront, wavefront grid 4 x 2 (256 features x 128
+// rows per workgroup: more workgroups, for a few hundred rows and for single-plane inputs), and GPW = 2,
+// wavefront grid 2 x 4 (256 features x 256 rows: fewer LDS bytes per matrix instruction).
+constexpr int LARGE_FEAT_GROUPS = 4;  // feature groups per workgroup (x 64 features), both shapes
+constexpr int large_row_groups(int gpw) { return gpw == 1 ? 2 : 4; }  // 64-row groups per workgroup
 
-template <int PLANES, int EPI>
+template <int PLANES, int EPI, int GPW>
 __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ part, int64_t part_stride,
                                                          const uint4* __restrict__ xp, const uint4* __restrict__ wp,
                                                          int RB, int N, int KT, int splits,
                                                          int* __restrict__ counters, GemmEpilogue epi) {
-  constexpr int FGS = LARGE_FGS, RGS = LARGE_RGS, CH = LARGE_CH;
+  constexpr int FGS = LARGE_FEAT_GROUPS / GPW, RGS = large_row_groups(GPW);
+  constexpr int CH = (PLANES == 2 && GPW == 2) ? 1 : 2;  // k steps per LDS stage
   static_assert(FGS * RGS == 8, "8 wavefronts");
-  constexpr int W_U4 = FGS * TN * 64;               // weights of one k step
+  constexpr int W_U4 = FGS * GPW * TN * 64;         // weights of one k step
   constexpr int X_U4 = RGS * 4 * PLANES * 64;       // activations of one k step
   constexpr int STEP_U4 = W_U4 + X_U4;
   constexpr int STAGE_U4 = CH * STEP_U4;
@@ -688,12 +695,10 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fg = wave % FGS, rg = wave / FGS;
   const int NG = (N + 16 * TN - 1) / (16 * TN);
-  const int ng_raw = blockIdx.x * FGS + fg;
-  const int ng = ng_raw < NG ? ng_raw : NG - 1;
+  const int g_first = (blockIdx.x * FGS + fg) * GPW;  // first feature group of this wavefront
   const int split = blockIdx.y;
   const int rb_tile = blockIdx.z * (RGS * 4);
   const int rbw = rb_tile + rg * 4;                 // first row block of this wavefront
-  const bool valid = ng_raw < NG && rbw < RB;
   const int groups = KT / PD;
   const int k_begin = (int)((int64_t)split * groups / splits) * PD;
   const int k_end = (int)((int64_t)(split + 1) * groups / splits) * PD;
@@ -709,7 +714,7 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
     const int ks = i / UPS, j = i % UPS;
     if (j < WUPS) {
       const int v = tid + j * 512;
-      const int g_raw = blockIdx.x * FGS + (v >> 8);
+      const int g_raw = blockIdx.x * (FGS * GPW) + (v >> 8);
       off[i] = ((((int64_t)(g_raw < NG ? g_raw : NG - 1) * KT + ks) * TN) << 6) + (v & 255);
     } else {
       const int xu = tid + (j - WUPS) * 512;
@@ -741,27 +746,31 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
   };
 #undef DED_EACH_UNIT
 
-  Acc acc;
+  Acc acc[GPW];
 #pragma unroll
-  for (int t = 0; t < TN; ++t)
+  for (int gw = 0; gw < GPW; ++gw)
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) acc[gw][t][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   auto compute = [&](int buf) {
 #pragma unroll
     for (int ks = 0; ks < CH; ++ks) {
-      const uint4* lw = lds[buf] + ks * STEP_U4 + fg * (TN * 64) + lane;
+      const uint4* lw = lds[buf] + ks * STEP_U4 + fg * (GPW * TN * 64) + lane;
       const uint4* lx = lds[buf] + ks * STEP_U4 + W_U4 + rg * (4 * PLANES * 64) + lane;
       f16x8_t b[4 * PLANES];
 #pragma unroll
       for (int i = 0; i < 4 * PLANES; ++i) b[i] = __builtin_bit_cast(f16x8_t, lx[i << 6]);
 #pragma unroll
-      for (int p = 0; p < PLANES; ++p)
+      for (int gw = 0; gw < GPW; ++gw)
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
-          f16x8_t a = __builtin_bit_cast(f16x8_t, lw[t << 6]);
+          f16x8_t a = __builtin_bit_cast(f16x8_t, lw[(gw * TN + t) << 6]);
 #pragma unroll
-          for (int rb = 0; rb < 4; ++rb)
-            acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[rb * PLANES + p], acc[t][rb], 0, 0, 0);
+          for (int p = 0; p < PLANES; ++p)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+              acc[gw][t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[rb * PLANES + p], acc[gw][t][rb], 0, 0, 0);
         }
     }
   };
@@ -785,12 +794,25 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
   __syncthreads();
   compute(buf ^ 1);  // last stage
 
-  const float row_scale = ssq_direct(epi, rbw < RB ? rbw : 0, lane);
-  if (splits == 1) {
-    if (valid) run_epilogue<EPI, 4>(epi, ng, N, rbw, rbw, row_scale, lane, acc);
-  } else if (finish_split(part, part_stride, split, splits, counters, NG, ng, rbw, lane, valid, acc, &s_flag) && valid) {
-    load_slices<4>(part, part_stride, splits, NG, ng, rbw, 0, lane, acc);
-    run_epilogue<EPI, 4>(epi, ng, N, rbw, rbw, row_scale, lane, acc);
+  // every wavefront finishes its own GPW tiles of 64 features x 64 rows
+  const bool rows_ok = rbw < RB;
+  const float row_scale = ssq_direct(epi, rows_ok ? rbw : 0, lane);
+  bool last = true;
+  if (splits > 1) {
+#pragma unroll
+    for (int gw = 1; gw < GPW; ++gw)
+      if (rows_ok && g_first + gw < NG) store_slice(part + (int64_t)split * part_stride, NG, g_first + gw, rbw, lane, acc[gw]);
+    last = finish_split(part, part_stride, split, splits, counters, NG, g_first < NG ? g_first : NG - 1, rbw, lane,
+                        rows_ok && g_first < NG, acc[0], &s_flag);
+  }
+  if (last && rows_ok) {
+#pragma unroll
+    for (int gw = 0; gw < GPW; ++gw) {
+      const int ng = g_first + gw;
+      if (ng >= NG) continue;
+      if (splits > 1) load_slices<4>(part, part_stride, splits, NG, ng, rbw, 0, lane, acc[gw]);
+      run_epilogue<EPI, 4>(epi, ng, N, rbw, rbw, row_scale, lane, acc[gw]);
+    }
   }
 }
 
@@ -825,9 +847,11 @@ bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float*
                   int nw, hipStream_t s) {
   const int splits = plan.splits;
 #define DED_ARGS part, part_stride, xp, wp, RB, N, KT, splits, counters, epi
-  if (plan.nwn == 8) {
-    dim3 grid(((N + 16 * TN - 1) / (16 * TN) + LARGE_FGS - 1) / LARGE_FGS, splits, (RB + 4 * LARGE_RGS - 1) / (4 * LARGE_RGS));
-    hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI>), grid, dim3(512), 0, s, DED_ARGS);
+  if (plan.nwn == 8 || plan.nwn == 9) {
+    const int rgs = large_row_groups(plan.nwn - 7);
+    dim3 grid(((N + 16 * TN - 1) / (16 * TN) + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS, splits, (RB + 4 * rgs - 1) / (4 * rgs));
+    if (plan.nwn == 8) hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI, 1>), grid, dim3(512), 0, s, DED_ARGS);
+    else hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI, 2>), grid, dim3(512), 0, s, DED_ARGS);
     return true;
   }
   if (plan.nwn == 0) {
@@ -850,11 +874,24 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
   static const Tune tune;
   const int NG = (N + 16 * TN - 1) / (16 * TN), groups = K / (32 * PD), rg = rows_pad / 64;
   const int64_t w_bytes = (int64_t)NG * 64 * K * 2, slice = (int64_t)rows_pad * N * 4;
-  if (rows_pad >= 256) {  // matrix-core bound: the large-row kernel; split k only to fill the chip
-    const int tiles = ((NG + LARGE_FGS - 1) / LARGE_FGS) * ((rows_pad + 64 * LARGE_RGS - 1) / (64 * LARGE_RGS));
-    int s = 1;
-    while (s < 8 && s < max_splits && s < groups && tiles * s < (kCUs * 3) / 4) ++s;
-    return GemmPlan{8, 1, s};
+  if (rows_pad >= 256) {  // matrix-core bound: the large-row kernel
+    // One workgroup per CU is resident, so a launch runs in ceil(workgroups / CUs) rounds.  The two-group
+    // wavefront tile pays off with two-plane inputs once there are enough row tiles (measured: from ~1024 rows);
+    // k is split only as far as it takes to fill the last round (a split costs its slices: 15 % per extra slice).
+    const int gpw = (planes == 2 && rows_pad >= 1024) ? 2 : 1;
+    const int tiles = ((NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS) *
+                      ((rows_pad + 64 * large_row_groups(gpw) - 1) / (64 * large_row_groups(gpw)));
+    GemmPlan best{7 + gpw, 1, 1};
+    double best_cost = 1e300;
+    for (int s = 1; s <= 4 && s <= max_splits && s <= groups; ++s) {
+      const int wgs = tiles * s, rounds = (wgs + kCUs - 1) / kCUs;
+      const double c = (double)rounds * kCUs / wgs * (1.0 + 0.15 * (s - 1));
+      if (c < best_cost) {
+        best_cost = c;
+        best.splits = s;
+      }
+    }
+    return best;
   }
   GemmPlan best{0, 1, 1};
   double best_cost = 1e300;
@@ -888,7 +925,10 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
 
 int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan) {
   const int NG = (N + 16 * TN - 1) / (16 * TN);
-  if (plan.nwn == 8) return ((NG + LARGE_FGS - 1) / LARGE_FGS) * ((rows_pad + 64 * LARGE_RGS - 1) / (64 * LARGE_RGS));
+  if (plan.nwn >= 8) {
+    const int rgs = large_row_groups(plan.nwn - 7);
+    return ((NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS) * ((rows_pad + 64 * rgs - 1) / (64 * rgs));
+  }
   const int gx = plan.nwn == 0 ? NG : (NG + plan.nwn - 1) / plan.nwn;
   return gx * (rows_pad / 64);
 }
@@ -901,7 +941,8 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
   const int NG = (N + 16 * TN - 1) / (16 * TN);
   const int splits = plan.splits;
   if (splits < 1 || splits > groups || !counters) return false;
-  if (plan.nwn != 0 && plan.nwn != 8 && groups / splits < 2) return false;
+  if (plan.nwn != 0 && plan.nwn < 8 && groups / splits < 2) return false;
+  if (plan.nwn > 9 || (plan.nwn == 9 && planes == 1)) return false;
   if (splits > 1 && part_stride < (int64_t)rows_pad * NG * 16 * TN) return false;
   if ((epi.kind == EPI_RESIDUAL || epi.kind == EPI_QKV || epi.kind == EPI_SILU) && N % 64) return false;
   int nw = plan.nw >= 4 ? 4 : plan.nw >= 2 ? 2 : 1;
