@@ -244,7 +244,7 @@ def large_rows_bench(di, steps=8):
         out.append({"workload": label, "rows": R, "executed_tflops": executed / (ms_total * 1e-3) / 1e12,
                     "useful_tflops": useful / (ms_total * 1e-3) / 1e12, "by_class": per})
     best = max(out, key=lambda o: o["executed_tflops"])
-    return {"bound": "mfma", "kernel": "gemm_large_kernel (128 features x 256 rows per workgroup), all projections of a step",
+    return {"bound": "mfma", "kernel": "gemm_large_kernel (256 features x 128 or 256 rows per workgroup), all projections of a step",
             "achieved": best["executed_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": best["executed_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "cases": out}
 
