@@ -245,27 +245,53 @@ __global__ __launch_bounds__(256) void tree_attn_partial_kernel(
   DED_ASTAMP(3)
 }
 
-// One workgroup of 128 threads per (row, query head): thread = head dim.
-__global__ __launch_bounds__(128) void tree_attn_merge_kernel(bf16_t* __restrict__ op, int RB,
+// One thread per (row, query head, 4 head dims).  The key ranges are folded in index order, eight at a time, with
+// all loads of a batch of eight in flight together; the result does not depend on the launch shape.
+__global__ __launch_bounds__(256) void tree_attn_merge_kernel(bf16_t* __restrict__ op, int RB,
                                                               const float* __restrict__ part_o,
                                                               const float2* __restrict__ part_ml, int n_splits,
-                                                              int n_step, int H) {
-  const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+                                                              int n_step, int H, int total) {
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  const int d4 = gid & 31, rh = gid >> 5;
+  const int r = rh / H, h = rh - r * H;
   const int b = r / n_step, node = r - b * n_step;
   const int64_t base = (((int64_t)b * H + h) * n_splits) * n_step + node;
-  float M = NEG_BIG;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[base + (int64_t)s * n_step].x);
-  float L = 0.f, acc = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    float2 ml = part_ml[base + (int64_t)s * n_step];
-    float w = __builtin_amdgcn_exp2f(ml.x - M);
-    L += ml.y * w;
-    acc += part_o[(base + (int64_t)s * n_step) * 128 + i] * w;
+  float M = NEG_BIG, L = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float2 ml[8];
+    float4 po[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int64_t row = base + (int64_t)min(s0 + j, n_splits - 1) * n_step;  // clamped: in bounds, weight 0 below
+      ml[j] = part_ml[row];
+      po[j] = *reinterpret_cast<const float4*>(part_o + row * 128 + d4 * 4);
+    }
+    float Mc = M;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < n_splits) Mc = fmaxf(Mc, ml[j].x);
+    const float keep = __builtin_amdgcn_exp2f(M - Mc);
+    L *= keep;
+    acc.x *= keep, acc.y *= keep, acc.z *= keep, acc.w *= keep;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float w = s0 + j < n_splits ? __builtin_amdgcn_exp2f(ml[j].x - Mc) : 0.f;
+      L += ml[j].y * w;
+      acc.x += po[j].x * w, acc.y += po[j].y * w, acc.z += po[j].z * w, acc.w += po[j].w * w;
+    }
+    M = Mc;
   }
-  uint16_t hi, lo;
-  split_f16(acc / L, hi, lo);
-  op[packx_index(r, h * 128 + i, RB, 0)] = hi;
-  op[packx_index(r, h * 128 + i, RB, 1)] = lo;
+  const float inv = 1.0f / L;
+  const float v[4] = {acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv};
+  uint16_t hi[4], lo[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_f16(v[i], hi[i], lo[i]);
+  // four consecutive features sit side by side inside a PackX fragment
+  const int64_t ihi = packx_index(r, h * 128 + d4 * 4, RB, 0), ilo = packx_index(r, h * 128 + d4 * 4, RB, 1);
+  *reinterpret_cast<uint2*>(op + ihi) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+  *reinterpret_cast<uint2*>(op + ilo) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
 }
 
 }  // namespace
@@ -276,7 +302,7 @@ int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int
   const int tiles = (max_p + m.n_step + TILE - 1) / TILE;
   const int base = m.batch * md.Hkv * row_tiles;
   int ns = std::max(1, 512 / std::max(base, 1));
-  ns = std::min(ns, std::max(1, tiles / 2));  // keep >= 2 tiles (128 keys) per range
+  ns = std::min(ns, std::max(1, tiles / 2));  // keep >= 2 tiles (128 keys) per range: each range re-reads the queries
   while (ns > 1 && (int64_t)m.batch * md.H * ns * m.n_step > part_rows_cap) --ns;
   return ns;
 }
@@ -297,8 +323,9 @@ void bf16_tree_attention_partial(const bf16_t* q_packed, const bf16_t* kc, const
 void bf16_tree_attention_merge(bf16_t* o_packed, int rows_pad, const float* part_o, const float2* part_ml,
                                int n_splits, const StepMeta& m, const ModelDims& md, hipStream_t s) {
   if (m.rows <= 0) return;
-  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(m.rows, md.H), dim3(128), 0, s, o_packed, rows_pad / 16, part_o,
-                     part_ml, n_splits, m.n_step, md.H);
+  const int total = m.rows * md.H * 32;
+  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((total + 255) / 256), dim3(256), 0, s, o_packed, rows_pad / 16,
+                     part_o, part_ml, n_splits, m.n_step, md.H, total);
 }
 
 }  // namespace ded
