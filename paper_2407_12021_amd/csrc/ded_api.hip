@@ -282,9 +282,10 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
   int32_t* amax = w.take<int32_t>(z.max_rows_pad);
   float* margin = w.take<float>(z.max_rows_pad);
   float* uniform = w.take<float>(z.max_rows_pad);
-  int32_t* nacc = w.take<int32_t>(c.max_batch);
-  int32_t* path = w.take<int32_t>((int64_t)c.max_batch * stride);
-  int32_t* acct = w.take<int32_t>((int64_t)c.max_batch * stride);
+  // one block, so that a single copy brings a step's verdict to the host: nacc | path | acctok
+  int32_t* nacc = w.take<int32_t>((int64_t)c.max_batch * (1 + 2 * stride));
+  int32_t* path = nacc + c.max_batch;
+  int32_t* acct = path + (int64_t)c.max_batch * stride;
   if (ctx) {
     ctx->d_meta = dmeta;
     ctx->meta_bytes = m;
@@ -763,11 +764,13 @@ int ded_accept(ded_ctx* c, int32_t mode, int32_t* accepted_tokens, int32_t* n_ac
   }
   if (launch_status() != DED_OK) return DED_EHIP;
   int32_t* h_n = reinterpret_cast<int32_t*>(c->h_res);
-  int32_t* h_path = h_n + B;
-  int32_t* h_tok = h_path + (size_t)B * stride;
-  HIP_TRY(hipMemcpyAsync(h_n, c->d_nacc, sizeof(int32_t) * B, hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipMemcpyAsync(h_path, c->d_path, sizeof(int32_t) * B * stride, hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipMemcpyAsync(h_tok, c->d_acctok, sizeof(int32_t) * B * stride, hipMemcpyDeviceToHost, s));
+  const int MB = c->cfg.max_batch;
+  int32_t* h_path = h_n + MB;
+  int32_t* h_tok = h_path + (size_t)MB * stride;
+  // nacc | path | acctok are one device block with the same layout: path and acctok of the live sequences end
+  // before (MB + (MB + B) * stride) words
+  HIP_TRY(hipMemcpyAsync(h_n, c->d_nacc, sizeof(int32_t) * ((size_t)MB + (size_t)(MB + B) * stride),
+                         hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
   for (int b = 0; b < B; ++b) {
     int len = h_n[b];
