@@ -8,7 +8,10 @@ Pinned parts (see tests/test_oracle_pins.py): every function below is pinned by 
 library special cases, brute force on tiny trees or the chain == autoregressive invariant; the
 pseudo-sequence builder by the set of root-to-node paths, hand-worked cases and the equality of a
 candidate's logits in the merged tree and in its own chain; the temperature / top-p sampler by brute
-force over subsets on tiny vocabularies, its limits (argmax, plain soft-max frequencies) and monotonicity.
+force over subsets on tiny vocabularies, its limits (argmax, plain soft-max frequencies) and monotonicity;
+the draft maker (tri-gram matrix, Adjust3Gram, search score, tree search) by a hand-worked corpus, hand-evaluated
+score values, a hand-traced first and second iteration, the closed form on a deterministic chain and the
+conservation of visits and scores over the search tree.
 Parity unpinned: none.
 """
 from .decoder import (  # noqa: F401
@@ -18,3 +21,4 @@ from .decoder import (  # noqa: F401
 from .accept import argmax_margin, accept_walk, compact_rows  # noqa: F401
 from .trie import build_trie  # noqa: F401
 from .sample import nucleus, sample_top_p, sample_rows  # noqa: F401
+from .drafter import TriGramMatrix, exploration_factor, puct, run_mcts  # noqa: F401

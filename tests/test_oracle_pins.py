@@ -540,3 +540,216 @@ def test_sampled_walk_reduces_to_greedy_and_uses_the_sampled_tokens():
         for a, b in zip(path, path[1:]):
             assert parent[b] == a and token[b] == model[a]
         assert acc[-1] == model[path[-1]] and not any(parent[c] == path[-1] and token[c] == model[path[-1]] for c in range(6))
+
+
+# ---------------------------------------------------------------- draft maker (Sec. 2.2, 2.3, Appendix G)
+from fractions import Fraction  # noqa: E402
+from oracle import drafter as dr  # noqa: E402
+
+HAND_CORPUS = [1, 2, 3, 1, 2, 4, 1, 2, 3, 1, 2]
+
+
+def _drafter_golden():
+    tri, pu = [], []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "drafter_cases.txt")):
+        line = line.strip()
+        if line.startswith("t:"):
+            head, body = line.split("->")
+            rows = {}
+            for part in body.split(";"):
+                if not part.strip():
+                    continue
+                ctx, succ = part.split(":")
+                rows[tuple(int(x) for x in ctx.split())] = [
+                    (int(s.split("=")[0]), Fraction(s.split("=")[1])) for s in succ.split()]
+            tri.append((int(head.split(":")[1]), rows))
+        elif line.startswith("puct:"):
+            a, b = line[5:].split("->")
+            pu.append(([float(x) for x in a.split()], [float(x) for x in b.split()]))
+    return tri, pu
+
+
+def test_trigram_matrix_hand_worked_and_threshold():
+    tri, _ = _drafter_golden()
+    assert len(tri) == 3
+    for t, rows in tri:
+        m = dr.TriGramMatrix()
+        m.count(HAND_CORPUS)
+        m.finalize(t)
+        assert list(m.matrix.keys()) == list(rows.keys())
+        for ctx, succ in rows.items():
+            got = m.successors(ctx)
+            assert [w for w, _ in got] == [w for w, _ in succ]  # order of first appearance
+            for (w, p), (_, f) in zip(got, succ):
+                assert p == float(f.numerator) / float(f.denominator)
+
+
+def test_trigram_matrix_sums_and_window_brute_force():
+    g = np.random.default_rng(0)
+    docs = [g.integers(0, 6, size=int(n)).tolist() for n in (200, 1, 2, 3, 57)]
+    m = dr.TriGramMatrix()
+    for d in docs:
+        m.count(d)
+    m.finalize(1)
+    import collections
+    windows = collections.Counter(tuple(d[i:i + 3]) for d in docs for i in range(len(d) - 2))
+    starts = collections.Counter(w[:2] for w in windows.elements())
+    assert sum(len(r) for r in m.matrix.values()) == len(windows)
+    for (a, b, c), k in windows.items():
+        assert m.prob((a, b), c) == k / starts[(a, b)]
+    for ctx, row in m.matrix.items():
+        assert abs(sum(row.values()) - 1.0) < 1e-12  # a context's tri-grams exhaust its bi-gram count
+    # elimination keeps the survivors' values and drops only tri-grams seen fewer than t times
+    m.finalize(4)
+    for (a, b, c), k in windows.items():
+        assert m.prob((a, b), c) == (k / starts[(a, b)] if k >= 4 else 0.0)
+    assert m.prob((99, 98), 1) == 0.0 and m.successors((99, 98)) == []
+
+
+def test_puct_hand_values_and_shape():
+    _, pu = _drafter_golden()
+    assert len(pu) == 4
+    for (q, p, n, s, c1, c2), (e, val) in pu:
+        assert abs(dr.exploration_factor(s, c1, c2) - e) <= 1e-13 * e
+        assert abs(dr.puct(q, p, n, s, c1, c2) - val) <= 1e-13 * val
+    # no visits at the node: the exploration term vanishes whatever the prior
+    assert dr.puct(1.75, 0.9, 0, 0, 32.0, 8.0) == 1.75
+    # grows with the prior and the parent's visits, shrinks with the action's own visits, Q enters additively
+    assert dr.puct(1.0, 0.6, 2, 9, 32.0, 8.0) > dr.puct(1.0, 0.5, 2, 9, 32.0, 8.0)
+    assert dr.puct(1.0, 0.5, 3, 9, 32.0, 8.0) < dr.puct(1.0, 0.5, 2, 9, 32.0, 8.0)
+    assert dr.puct(1.0, 0.5, 2, 16, 32.0, 8.0) > dr.puct(1.0, 0.5, 2, 9, 32.0, 8.0)
+    assert abs((dr.puct(3.0, 0.5, 2, 9, 32.0, 8.0) - dr.puct(1.0, 0.5, 2, 9, 32.0, 8.0)) - 2.0) < 1e-12
+    assert dr.exploration_factor(0, 32.0, 8.0) == 32.0 + np.log(9.0 / 8.0)
+    # a prior of zero or the doubling of (1 + N): exact ratios
+    assert dr.puct(0.0, 0.0, 5, 9, 32.0, 8.0) == 0.0
+    assert abs(dr.puct(0.0, 0.4, 1, 9, 32.0, 8.0) / dr.puct(0.0, 0.4, 3, 9, 32.0, 8.0) - 2.0) < 1e-12
+
+
+def test_adjust_3gram_hand_case():
+    m = dr.TriGramMatrix()
+    m.count(HAND_CORPUS)
+    m.finalize(1)
+    before = {k: dict(v) for k, v in m.matrix.items()}
+    # only the last max_length = 4 tokens count: tri-grams (1,2,3) and (2,3,7); (9,1,2) lies outside the window
+    m.adjust_3gram([9, 1, 2, 3, 7], max_length=4, increment=0.5, max_prob=0.9)
+    assert m.prob((1, 2), 3) == 0.9                 # 2/3 + 0.5 capped
+    assert m.prob((1, 2), 4) == before[(1, 2)][4]   # untouched
+    assert m.successors((2, 3)) == [(1, 1.0), (7, 0.5)]  # new tri-gram appended with the increment
+    assert (9, 1) not in m.matrix
+    m.adjust_3gram([2, 3, 7], max_length=10, increment=0.25, max_prob=0.9)
+    assert m.prob((2, 3), 7) == 0.75
+    m.adjust_3gram([2, 3, 7], max_length=10, increment=0.25, max_prob=0.9)
+    m.adjust_3gram([2, 3, 7], max_length=10, increment=0.25, max_prob=0.9)
+    assert m.prob((2, 3), 7) == 0.9                 # stays at the cap
+    m.adjust_3gram([5, 6, 5], max_length=10, increment=0.25, max_prob=0.9)
+    assert m.successors((5, 6)) == [(5, 0.25)]      # a new context
+    snap = {k: dict(v) for k, v in m.matrix.items()}
+    m.adjust_3gram([5, 6], max_length=10, increment=0.25, max_prob=0.9)   # too short for a tri-gram
+    m.adjust_3gram([1, 2, 3, 1], max_length=2, increment=0.25, max_prob=0.9)  # window too short
+    assert snap == m.matrix
+
+
+def _chain_matrix(words):
+    m = dr.TriGramMatrix()
+    for i in range(2, len(words)):
+        m.matrix[(words[i - 2], words[i - 1])] = {words[i]: 1.0}
+    return m
+
+
+def _tree_nodes(root):
+    out, stack = [], [root]
+    while stack:
+        nd = stack.pop()
+        out.append(nd)
+        stack.extend(nd.children)
+    return out
+
+
+def test_mcts_on_a_deterministic_chain_closed_form():
+    words = [10, 11, 12, 13, 14, 15, 16, 17]
+    m = _chain_matrix(words)
+    iters, l = 20, 4
+    sent, root = dr.run_mcts(m, 10, 11, [0.5] * (iters * l), iterations=iters, l=l, n=24, return_root=True)
+    # one path; an iteration scores 1 + l; depth d is created by iteration d, so the depth-l leaf is passed
+    # by iterations l .. iters
+    assert sent == [((1.0 + l) * (iters - l + 1), [12, 13, 14, 15])]
+    assert root.visits == iters and root.score == (1.0 + l) * iters
+    # a chain that ends early: the sentence is what exists, an iteration scores 1 + (words found)
+    sent = dr.run_mcts(_chain_matrix([1, 2, 3, 4]), 1, 2, [0.5] * 40, iterations=10, l=4, n=24)
+    assert sent == [(3.0 * 9, [3, 4])]
+    assert dr.run_mcts(m, 98, 99, [0.5] * 40, iterations=10, l=4) == []  # unknown context: nothing to propose
+
+
+def test_mcts_first_iteration_by_hand_and_inverse_cdf():
+    m = dr.TriGramMatrix()
+    m.matrix[(1, 2)] = {3: 0.25, 4: 0.75}
+    m.matrix[(2, 4)] = {5: 0.5, 6: 0.3, 7: 0.2}
+    m.matrix[(2, 3)] = {8: 1.0}
+    # iteration 0: the root is expanded into [3, 4], the search continues with the last child (4) and
+    # simulates one word after the pair (2, 4); l = 2, so the draw uses uniform[0 * 2 + 1]
+    for u, pick, p_pick in ((0.0, 5, 0.5), (0.49, 5, 0.5), (0.5, 6, 0.3), (0.79, 6, 0.3), (0.8, 7, 0.2), (0.999, 7, 0.2)):
+        _, root = dr.run_mcts(m, 1, 2, [0.123, u], iterations=1, l=2, return_root=True)
+        assert [c.word for c in root.children] == [(2, 3), (2, 4)]
+        assert [c.visits for c in root.children] == [0, 1]
+        assert abs(root.score - (1.0 + 0.75 + p_pick)) < 1e-15, (u, pick)
+    # unnormalised successors (after an update): weights are relative to their sum 1.5
+    m.matrix[(2, 4)] = {5: 0.9, 6: 0.6}
+    for u, p_pick in ((0.59, 0.9), (0.61, 0.6)):
+        _, root = dr.run_mcts(m, 1, 2, [0.0, u], iterations=1, l=2, return_root=True)
+        assert abs(root.score - (1.0 + 0.75 + p_pick)) < 1e-15
+    # iteration 1 selects among root's children by Eq. (2): child 3 (unvisited, prior .25) against child 4
+    # (one visit, Q = 2.65, prior .75), sum N = 1, C1 = 32, C2 = 8:  8.06 < 2.65 + 12.08 -> child 4 again,
+    # which is expanded ([5, 6], last child 6 visited).  With C1 = 0.5 and C2 = 8 the values are 0.59 and 1.17 +
+    # Q: still child 4; lowering Q's weight is impossible, so make child 3's prior dominate instead.
+    _, root = dr.run_mcts(m, 1, 2, [0.0, 0.0, 0.0, 0.0], iterations=2, l=2, return_root=True)
+    assert [c.visits for c in root.children] == [0, 2]
+    assert [c.visits for c in root.children[1].children] == [0, 1]
+    m.matrix[(1, 2)] = {3: 0.9, 4: 0.1}
+    _, root = dr.run_mcts(m, 1, 2, [0.0, 0.0, 0.0, 0.0], iterations=2, l=2, return_root=True)
+    # child 4: Q = 1 + .1 + .9 = 2.0, U = 32.22 * .1 * 1 / 2 = 1.61 -> 3.61;  child 3: 32.22 * .9 = 29.0
+    assert [c.visits for c in root.children] == [1, 1]
+
+
+def test_mcts_invariants_on_random_matrices():
+    g = np.random.default_rng(5)
+    for case in range(6):
+        V = int(g.integers(4, 9))
+        m = dr.TriGramMatrix()
+        m.count(g.integers(0, V, size=600).tolist())
+        m.finalize(int(g.integers(1, 4)))
+        if case % 2:
+            m.adjust_3gram(g.integers(0, V, size=40).tolist(), 30, 0.3, 0.95)
+        iters, l, n = int(g.integers(1, 200)), int(g.integers(1, 6)), int(g.integers(1, 30))
+        ctx = next(iter(m.matrix))
+        u = g.random(iters * l)
+        sent, root = dr.run_mcts(m, ctx[0], ctx[1], u, iterations=iters, l=l, n=n, return_root=True)
+        nodes = _tree_nodes(root)
+        assert root.visits == iters
+        max_p = max(p for row in m.matrix.values() for p in row.values())
+        assert iters * 1.0 <= root.score <= iters * (1.0 + l * max_p) + 1e-9
+        leaves = 0
+        for nd in nodes:
+            if nd.children:
+                # every iteration that reaches an expanded node goes on to one of its children; the one
+                # exception is the iteration that created the node as its parent's last child and stopped there
+                own = 1 if nd.parent is not None and nd.parent.children[-1] is nd else 0
+                assert nd.visits == sum(c.visits for c in nd.children) + own
+                assert nd.score >= sum(c.score for c in nd.children) - 1e-9
+                if not own:
+                    assert abs(nd.score - sum(c.score for c in nd.children)) < 1e-9 * max(1.0, nd.score)
+                assert not nd.untried_words
+                assert [c.word[1] for c in nd.children] == [w for w, _ in m.successors(nd.word)]
+            else:
+                leaves += 1
+        assert len(sent) == min(n, leaves if root.children else 0)
+        scores = [s for s, _ in sent]
+        assert scores == sorted(scores, reverse=True)
+        for s, words in sent:
+            assert 1 <= len(words) <= l
+            a, b = ctx
+            for w in words:  # a path of the tri-gram matrix
+                assert m.prob((a, b), w) > 0.0
+                a, b = b, w
+        # same inputs, same result (no hidden randomness)
+        again = dr.run_mcts(m, ctx[0], ctx[1], u, iterations=iters, l=l, n=n)
+        assert again == sent
