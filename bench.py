@@ -105,57 +105,87 @@ def time_steps(ver, P, parent, tokens_list, steps, warmup):
 
 
 def decode_loop_bench(di, ver, wl, prefix, root, n_new=48, seed=2):
-    """End-to-end decoding from the resident 1024-token prefix: every step builds 24 candidate continuations
-    of length 4 (the paper's n and l) from the synthetic tri-gram model, merges them with ded_build_tree
-    (budget = the context's 64 nodes), verifies the tree and commits the accepted tokens.  As a random-init
-    model never agrees with tri-gram drafts, the first candidate carries the model's own continuation (from
-    a plain one-token-per-step pass through the same library) for m ~ Geometric tokens.  The output must
-    equal that plain greedy continuation token for token."""
+    """End-to-end decoding from the resident 1024-token prefix with the whole loop of the method: every step the
+    C++ draft maker searches the tri-gram matrix (150 iterations, n = 24 candidates of l = 4 words, C1 = 32, C2 = 8,
+    elimination threshold 12), ded_build_tree merges the candidates (budget = the context's 64 nodes), the tree is
+    verified, the accepted tokens are committed and fed back through Adjust3Gram.
+    A random-init model agrees with no corpus, so the synthetic corpus is made to resemble the model's output the
+    way the paper's corpora resemble an LLM's: for every context of the model's own greedy continuation (from a
+    plain one-token-per-step pass through the same library) it holds the true next token among that context's
+    synthetic successors, with a share of the context's 200 occurrences drawn from {0.05, 0.2, 0.5} (0.05 falls
+    under the threshold), and three levels of synthetic continuations of the wrong successors.  What is accepted
+    is whatever the search finds.
+    The output must equal the plain greedy continuation token for token."""
     import numpy as np
     from paper_2407_12021_amd import binding as B
     P = len(prefix)
+    import torch
     ref, r, p = [], int(root), P
-    while len(ref) < n_new + wl.depth + 8:  # plain greedy decoding
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while len(ref) < n_new + wl.depth + 8:  # plain greedy decoding, one token per step
         ver.verify_step([p], [[-1]], [[r]])
         acc, _, newp = ver.accept(mode=0)
         r, p = acc[0][0], newp[0]
         ref.append(r)
+    plain_tokens_per_s = len(ref) / (time.perf_counter() - t0)
     tri = di.SyntheticTrigram(wl.model.vocab, seed=0)
     g = np.random.default_rng(seed)
-    out, steps, nodes = [], 0, 0
+    drafter = B.Drafter()
+
+    def add_context(a, c, true, levels):
+        """Counts for the context (a, c): its synthetic successors share 200 occurrences (minus the true token's
+        share); successors frequent enough to survive the threshold get continuations of their own."""
+        succ, prob = tri.successors(a, c)
+        share = float(g.choice([0.05, 0.2, 0.5])) if true is not None else 0.0
+        for x, px in zip(succ.tolist(), prob.tolist()):
+            if x == true:
+                continue
+            k = int(round(200 * px * (1.0 - share)))
+            drafter.count([a, c, x], k)
+            if levels > 0 and k >= 12:
+                add_context(c, x, None, levels - 1)
+        if true is not None:
+            drafter.count([a, c, true], int(round(200 * share)))
+
+    seq = [int(prefix[-1]), int(root)] + ref
+    for i in range(2, len(seq)):
+        add_context(seq[i - 2], seq[i - 1], seq[i], 3)
+    drafter.finalize(12)
+    out, steps, nodes, n_cands = [], 0, 0, 0
     prev, r, p = int(prefix[-1]), int(root), P
-    t_build = 0.0
-    import torch
+    t_draft = t_tree = 0.0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     while len(out) < n_new:
         tb = time.perf_counter()
-        cands = []
-        for c in range(24):
-            a, b, seq = prev, r, []
-            for _ in range(4):
-                succ, prob = tri.successors(a, b)
-                t = int(succ[g.choice(len(succ), p=prob)])
-                seq.append(t)
-                a, b = b, t
-            cands.append(seq)
-        m = min(int(g.geometric(0.42)) - 1, 4)
-        cands[0] = ref[len(out):len(out) + m] + cands[0][m:]
+        cands = [w for _, w in drafter.mcts(prev, r, g.random(600), iterations=150, l=4, n=24, c1=32.0, c2=8.0)]
+        tc = time.perf_counter()
         rc, parent, token, _ = B.ded_build_tree(r, cands, wl.n_nodes)
         assert rc == B.DED_OK
-        t_build += time.perf_counter() - tb
+        t_draft += tc - tb
+        t_tree += time.perf_counter() - tc
         ver.verify_step([p], [parent], [token])
         acc, _, newp = ver.accept(mode=0)
         out += acc[0]
+        tb = time.perf_counter()
+        drafter.adjust(([prev, r] + acc[0])[-34:], 34, 0.1, 1.0)  # Adjust3Gram on what was just committed
+        t_draft += time.perf_counter() - tb
         prev = acc[0][-2] if len(acc[0]) > 1 else r
         r, p = acc[0][-1], newp[0]
         steps += 1
         nodes += len(parent)
+        n_cands += len(cands)
     dt = time.perf_counter() - t0
     lossless = out[:n_new] == ref[:n_new]
+    trigrams = drafter.size()
+    drafter.close()
     return {"tokens": len(out), "steps": steps, "tokens_per_s": len(out) / dt, "steps_per_s": steps / dt,
+            "plain_greedy_tokens_per_s": plain_tokens_per_s, "speedup_vs_plain_greedy": len(out) / dt / plain_tokens_per_s,
             "mean_accepted_per_step": len(out) / steps, "mean_tree_nodes": nodes / steps,
-            "host_draft_and_tree_build_share": t_build / dt, "lossless_vs_plain_greedy": bool(lossless)}
+            "mean_candidates": n_cands / steps, "trigrams_in_matrix": trigrams,
+            "draft_maker_us_per_step": 1e6 * t_draft / steps, "tree_build_us_per_step": 1e6 * t_tree / steps,
+            "host_draft_and_tree_build_share": (t_draft + t_tree) / dt, "lossless_vs_plain_greedy": bool(lossless)}
 
 
 def attention_only_bench(di, iters=40):

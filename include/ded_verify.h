@@ -120,6 +120,60 @@ int ded_build_tree(int32_t root_token, int32_t n_cand, const int32_t *cand_len, 
                    int32_t max_len, int32_t max_nodes, int32_t *parent, int32_t *token,
                    int32_t *cand_end, int32_t *n_nodes);
 
+/* ---- Draft maker (host only, touches no device; the paper runs it on the CPU beside the verification step) ----
+ *
+ * ded_trigram is the LLM representative of Sec. 2.2: for a context (w_{i-2}, w_{i-1}) the words that may follow and
+ * their probabilities.  The successors of a context keep their order of first appearance (corpus order, then the
+ * insertions of ded_trigram_adjust); that order fixes expansion order, tie breaks and the inverse CDF below.
+ * All probabilities and scores are double precision.  A ded_trigram is not thread safe. */
+typedef struct ded_trigram ded_trigram;
+
+/* NULL if the host is out of memory.  ded_trigram_free accepts NULL. */
+ded_trigram *ded_trigram_create(void);
+void ded_trigram_free(ded_trigram *m);
+
+/* Adds the tri-grams of one document (host [n] token ids; n < 3 adds nothing) to the counts C(w_{i-2}, w_{i-1}, w_i)
+ * and C(w_{i-2}, w_{i-1}) of Eq. (1); the bi-gram count is the number of tri-grams that start with the pair.
+ * `times` >= 0 counts the document as if it occurred that often in the corpus.
+ * Errors: DED_EINVAL, DED_ENOMEM. */
+int ded_trigram_count(ded_trigram *m, const int32_t *tokens, int64_t n, int64_t times);
+
+/* (Re)builds the matrix from the counts: P = C(w_{i-2}, w_{i-1}, w_i) / C(w_{i-2}, w_{i-1}) (Eq. (1)) for every
+ * tri-gram counted at least t times (the elimination threshold of Appendix F.1, t = 12 there; survivors are not
+ * re-normalised, contexts left without successors disappear).  Discards earlier ded_trigram_adjust updates. */
+int ded_trigram_finalize(ded_trigram *m, int32_t t);
+
+/* Adjust3Gram (Appendix G, Alg. 2): for every tri-gram inside the last max_length tokens of `tokens` (host [n]):
+ * p <- min(p + increment, max_prob), or p <- increment for a tri-gram that is new (appended to its context, which
+ * is created if needed).  The paper gives no values for increment, max_prob and max_length. */
+int ded_trigram_adjust(ded_trigram *m, const int32_t *tokens, int64_t n, int64_t max_length, double increment,
+                       double max_prob);
+
+/* Successors of (w0, w1): *n_out = how many there are; the first min(cap, *n_out) go to words / probs (host). */
+int ded_trigram_lookup(const ded_trigram *m, int32_t w0, int32_t w1, int32_t cap, int32_t *words, double *probs,
+                       int32_t *n_out);
+
+/* Number of tri-grams in the matrix (negative: DED_EINVAL). */
+int64_t ded_trigram_size(const ded_trigram *m);
+
+/* The draft search of Sec. 2.3 / Appendix G, Alg. 1 from the last two tokens (w0, w1) of the sequence:
+ * `iterations` rounds of selection by the score of Eq. (2), (3)
+ *     PUCT(s,a) = Q(s,a) + E P(s,a) sqrt(sum_b N(s,b)) / (1 + N(s,a)),  E = c1 + log((sum_b N(s,b) + c2 + 1) / c2)
+ * (Q = accumulated score / visits of the child, 0 if unvisited; P = its tri-gram probability; first child wins a
+ * tie), expansion (all successors at once, the search goes on with the one created last), simulation up to l words
+ * (inverse CDF over the successors in stored order, weights relative to their sum, with
+ * uniform[iteration * l + words already in the sentence]) and back-propagation of 1 + the sum of the sentence's
+ * tri-gram probabilities.  The root-to-leaf paths of the search tree, ranked by the leaf's accumulated score
+ * (depth-first order among equals), are the candidates; the best n are returned.
+ *   uniform      host [n_uniform] numbers in [0, 1), n_uniform >= iterations * l; the caller owns the randomness
+ *   cand_tokens  host output [n][l]; cand_len [n] words of each candidate (1..l); cand_score [n] or NULL
+ *   n_cand       host output: candidates written (0 if the context (w0, w1) is unknown)
+ * Appendix F.1 uses iterations = 150, l = 4, n = 24, c1 = 32, c2 = 8.
+ * Errors: DED_EINVAL (null, l < 1, c2 <= 0, too few uniforms), DED_ENOMEM. */
+int ded_draft_mcts(const ded_trigram *m, int32_t w0, int32_t w1, int32_t iterations, int32_t l, int32_t n,
+                   double c1, double c2, const double *uniform, int64_t n_uniform, int32_t *cand_tokens,
+                   int32_t *cand_len, double *cand_score, int32_t *n_cand);
+
 /* Creates a context: validates cfg, re-lays out the weights into `workspace` (device, 256-byte
  * aligned, >= ded_workspace_bytes) on `hip_stream` (a hipStream_t; NULL = the default stream) and
  * waits for that to finish.  The workspace and KV buffers must outlive the context; their contents

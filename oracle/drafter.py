@@ -48,13 +48,15 @@ class TriGramMatrix:
         self.c2: Dict[Pair, int] = {}              # C(w_{i-2}, w_{i-1})
         self.matrix: Dict[Pair, Dict[int, float]] = {}
 
-    def count(self, tokens: Sequence[int]) -> None:
-        """Adds one document's tri-grams to the counts (T1)."""
+    def count(self, tokens: Sequence[int], times: int = 1) -> None:
+        """Adds one document's tri-grams to the counts (T1), as if the document occurred `times` times."""
+        if times <= 0:
+            return
         for i in range(2, len(tokens)):
             ctx = (int(tokens[i - 2]), int(tokens[i - 1]))
             row = self.c3.setdefault(ctx, {})
-            row[int(tokens[i])] = row.get(int(tokens[i]), 0) + 1
-            self.c2[ctx] = self.c2.get(ctx, 0) + 1
+            row[int(tokens[i])] = row.get(int(tokens[i]), 0) + times
+            self.c2[ctx] = self.c2.get(ctx, 0) + times
 
     def finalize(self, t: int = 12) -> None:
         """Eq. (1) for every counted tri-gram, then the elimination threshold (T2)."""

@@ -4,4 +4,4 @@
 shared library in-tree.  Nothing here falls back to a CPU path: without the library every call raises.
 """
 from . import binding  # noqa: F401
-from .binding import Verifier, DedError  # noqa: F401
+from .binding import Verifier, Drafter, DedError  # noqa: F401

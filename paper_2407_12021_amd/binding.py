@@ -23,6 +23,8 @@ EXPORTS = [
     "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_build_tree", "ded_verify_init", "ded_verify_free",
     "ded_verify_step", "ded_sample", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
     "ded_profile_enable", "ded_profile_read", "ded_strerror",
+    "ded_trigram_create", "ded_trigram_free", "ded_trigram_count", "ded_trigram_finalize", "ded_trigram_adjust",
+    "ded_trigram_lookup", "ded_trigram_size", "ded_draft_mcts",
 ]
 
 
@@ -70,6 +72,24 @@ def lib() -> C.CDLL:
         L.ded_sample.argtypes = [vp, C.c_float, C.c_float, C.POINTER(C.c_float)]
         L.ded_build_tree.restype = C.c_int
         L.ded_build_tree.argtypes = [C.c_int32, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
+        f64p = C.POINTER(C.c_double)
+        L.ded_trigram_create.restype = vp
+        L.ded_trigram_create.argtypes = []
+        L.ded_trigram_free.restype = None
+        L.ded_trigram_free.argtypes = [vp]
+        L.ded_trigram_count.restype = C.c_int
+        L.ded_trigram_count.argtypes = [vp, i32p, C.c_int64, C.c_int64]
+        L.ded_trigram_finalize.restype = C.c_int
+        L.ded_trigram_finalize.argtypes = [vp, C.c_int32]
+        L.ded_trigram_adjust.restype = C.c_int
+        L.ded_trigram_adjust.argtypes = [vp, i32p, C.c_int64, C.c_int64, C.c_double, C.c_double]
+        L.ded_trigram_lookup.restype = C.c_int
+        L.ded_trigram_lookup.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, i32p, f64p, i32p]
+        L.ded_trigram_size.restype = C.c_int64
+        L.ded_trigram_size.argtypes = [vp]
+        L.ded_draft_mcts.restype = C.c_int
+        L.ded_draft_mcts.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double, C.c_double,
+                                     f64p, C.c_int64, i32p, i32p, f64p, i32p]
         L.ded_verify_init.restype = C.c_int
         L.ded_verify_init.argtypes = [C.POINTER(ded_config), C.POINTER(ded_weights), C.POINTER(ded_kv), vp,
                                       C.c_size_t, vp, C.POINTER(vp)]
@@ -152,6 +172,69 @@ def ded_build_tree(root_token: int, candidates, max_nodes: int):
     rc = int(lib().ded_build_tree(int(root_token), n, _p32(lens), _p32(toks), max(max_len, 1) if n else 0, int(max_nodes),
                                   _p32(parent), _p32(token), _p32(end), C.byref(nn)))
     return rc, parent[: nn.value].copy(), token[: nn.value].copy(), end[:n].copy()
+
+
+class Drafter:
+    """The CPU draft maker behind the C-ABI: tri-gram matrix + tree search (argument marshalling only)."""
+
+    def __init__(self):
+        self._m = lib().ded_trigram_create()
+        if not self._m:
+            raise DedError(DED_ENOMEM, "ded_trigram_create")
+
+    def close(self):
+        if getattr(self, "_m", None):
+            lib().ded_trigram_free(self._m)
+            self._m = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _check(rc, where):
+        if rc != DED_OK:
+            raise DedError(rc, where)
+
+    def count(self, tokens, times: int = 1):
+        t = _i32(tokens)
+        self._check(lib().ded_trigram_count(self._m, _p32(t), len(t), int(times)), "ded_trigram_count")
+
+    def finalize(self, t: int = 12):
+        self._check(lib().ded_trigram_finalize(self._m, int(t)), "ded_trigram_finalize")
+
+    def adjust(self, tokens, max_length: int, increment: float, max_prob: float):
+        t = _i32(tokens)
+        self._check(lib().ded_trigram_adjust(self._m, _p32(t), len(t), int(max_length), float(increment),
+                                             float(max_prob)), "ded_trigram_adjust")
+
+    def successors(self, w0: int, w1: int):
+        n = C.c_int32(0)
+        self._check(lib().ded_trigram_lookup(self._m, int(w0), int(w1), 0, None, None, C.byref(n)), "ded_trigram_lookup")
+        words = np.zeros(max(n.value, 1), np.int32)
+        probs = np.zeros(max(n.value, 1), np.float64)
+        self._check(lib().ded_trigram_lookup(self._m, int(w0), int(w1), n.value, _p32(words),
+                                             probs.ctypes.data_as(C.POINTER(C.c_double)), C.byref(n)), "ded_trigram_lookup")
+        return [(int(w), float(p)) for w, p in zip(words[: n.value], probs[: n.value])]
+
+    def size(self) -> int:
+        return int(lib().ded_trigram_size(self._m))
+
+    def mcts(self, w0: int, w1: int, uniform, iterations: int = 150, l: int = 4, n: int = 24, c1: float = 32.0,
+             c2: float = 8.0):
+        """Returns [(score, [words])], best first."""
+        u = np.ascontiguousarray(uniform, dtype=np.float64)
+        toks = np.zeros((max(n, 1), l), np.int32)
+        lens = np.zeros(max(n, 1), np.int32)
+        score = np.zeros(max(n, 1), np.float64)
+        nc = C.c_int32(0)
+        f64p = C.POINTER(C.c_double)
+        self._check(lib().ded_draft_mcts(self._m, int(w0), int(w1), int(iterations), int(l), int(n), float(c1), float(c2),
+                                         u.ctypes.data_as(f64p), len(u), _p32(toks), _p32(lens),
+                                         score.ctypes.data_as(f64p), C.byref(nc)), "ded_draft_mcts")
+        return [(float(score[i]), toks[i, : lens[i]].tolist()) for i in range(nc.value)]
 
 
 def ded_verify_init(cfg: ded_config, weights: ded_weights, kv: ded_kv, workspace_ptr: int, workspace_bytes: int,

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libded_verify.so")
 SOURCES = ["ded_api.hip", "kernels_shared.hip", "kernels_f32.hip", "kernels_bf16.hip", "gemm_bf16.hip",
-           "attn_bf16.hip", "tree_builder.hip"]
+           "attn_bf16.hip", "tree_builder.hip", "drafter.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -184,6 +184,63 @@ def test_lossless_multi_step_decode(dtype):
     ver.close()
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_whole_loop_with_the_draft_maker_is_lossless(dtype):
+    """The method end to end (Fig. 2 / Appendix H data flow): tri-gram matrix -> tree search -> pseudo-sequence ->
+    verification -> approval -> Adjust3Gram, every part behind the C ABI.  The corpus holds the oracle's own greedy
+    continuation among distractors, so some drafts are right and some are wrong; whatever is proposed, the output
+    must be the oracle's plain autoregressive decoding (Sec. 2.4), and the matrix must have learnt the output."""
+    from paper_2407_12021_amd import binding as B
+    hd = 128 if dtype == "bf16" else 32
+    cfg = di.ModelConfig("loop-" + dtype, 2, 128, 2, 2, hd, 256, 512, dtype=dtype)
+    w = di.make_weights(cfg, seed=13, gain_jitter=0.1, std=0.3)
+    prompt = di.zipf_tokens(cfg.vocab, 9, seed=13).tolist()
+    n_new = 24
+    seq, ar, margins = list(prompt), [], []
+    for _ in range(n_new + 6):
+        lg = oracle.autoregressive_logits(cfg, w, seq)[-1]
+        a, m = oracle.argmax_margin(lg[None])
+        ar.append(int(a[0]))
+        margins.append(float(m[0]))
+        seq.append(int(a[0]))
+    g = np.random.default_rng(1)
+    drafter = B.Drafter()
+    for i in range(len(prompt), len(seq)):  # the true tri-gram among 3 wrong successors; weak every third position
+        a, c, true = seq[i - 2], seq[i - 1], seq[i]
+        for x in g.choice(cfg.vocab, size=3, replace=False).tolist():
+            if x != true:
+                drafter.count([a, c, x], 20)
+                drafter.count([c, x, int(g.integers(0, cfg.vocab))], 15)
+        drafter.count([a, c, true], 6 if i % 3 == 0 else 30)  # 6 < t: eliminated, the draft breaks there
+    drafter.finalize(12)
+    ver = _verifier(cfg, w, max_batch=1, kv_capacity=256, max_nodes=16)
+    gpu_prefill(ver, [np.array(prompt[:-1], np.int32)])
+    P, prev, root, produced, accepted_drafts, steps = len(prompt) - 1, prompt[-2], prompt[-1], [], 0, 0
+    while len(produced) < n_new:
+        cands = [wd for _, wd in drafter.mcts(prev, root, g.random(60 * 3), iterations=60, l=3, n=8)]
+        rc, parent, token, _ = B.ded_build_tree(root, cands, 16)
+        assert rc == B.DED_OK
+        ver.verify_step([P], [parent], [token])
+        acc, path, newp = ver.accept(mode=0)
+        produced.extend(acc[0])
+        accepted_drafts += len(acc[0]) - 1
+        drafter.adjust([prev, root] + acc[0], 16, 0.25, 1.0)
+        prev = acc[0][-2] if len(acc[0]) > 1 else root
+        P, root = newp[0], acc[0][-1]
+        steps += 1
+    first_unsure = next((i for i, mg in enumerate(margins) if mg <= MARGIN), n_new)
+    assert produced[:first_unsure] == ar[:first_unsure]
+    assert first_unsure >= 12, "test model too flat to say anything"
+    assert accepted_drafts >= 4 and steps < n_new, (accepted_drafts, steps)  # the search found real drafts
+    # self-improvement: every tri-gram of the committed output is now in the matrix with at least the increment
+    out = prompt[-2:] + produced
+    for i in range(2, len(out)):
+        p_i = dict(drafter.successors(out[i - 2], out[i - 1])).get(out[i], 0.0)
+        assert p_i >= 0.25, (i, p_i)
+    drafter.close()
+    ver.close()
+
+
 @pytest.mark.parametrize("dtype,P,N,H,Hkv", [("fp32", 100, 20, 4, 2), ("bf16", 333, 50, 4, 2), ("bf16", 0, 16, 2, 2)])
 def test_tree_attention_only(dtype, P, N, H, Hkv):
     """The attention layer on its own with injected q / K / V (config-2 style, small)."""
