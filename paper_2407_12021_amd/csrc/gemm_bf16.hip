@@ -102,6 +102,80 @@ __device__ inline void load_slices(const float* part, int64_t part_stride, int s
   }
 }
 
+// The same for a wavefront that holds only RBN row blocks of its tile (first one: rb_lo) in acc[t][0 .. RBN-1].
+template <int RBN>
+__device__ inline void store_slice_rows(float* slice, int NG, int ng, int rb0, int rb_lo, int lane, const Acc& acc) {
+  unsigned long long* q =
+      reinterpret_cast<unsigned long long*>(slice + slice_tile_offset(rb0, NG, ng) + rb_lo * 256) + lane;
+#pragma unroll
+  for (int t = 0; t < TN; ++t)
+#pragma unroll
+    for (int j = 0; j < RBN; ++j) {
+      const f32x4_t v = acc[t][j];
+      __hip_atomic_store(q + (t * 4 + j) * 128, pack2(v[0], v[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(q + (t * 4 + j) * 128 + 64, pack2(v[2], v[3]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// acc[t][j] (in: this workgroup's own slice values, which it still holds) = sum over slices 0..S-1 in slice order,
+// the own values standing in for slice `split`: only the S - 1 other slices are fetched, all loads in flight
+// together.  The result does not depend on which workgroup arrived last.
+template <int RBN, int S>
+__device__ inline void sum_other_slices(const float* part, int64_t part_stride, int split, int NG, int ng, int rb0,
+                                        int rb_lo, int lane, Acc& acc) {
+  const float* base = part + slice_tile_offset(rb0, NG, ng) + rb_lo * 256;
+  unsigned long long a[S - 1][TN][RBN], b[S - 1][TN][RBN];
+#pragma unroll
+  for (int k = 0; k < S - 1; ++k) {
+    const int sl = k + (k >= split ? 1 : 0);
+    unsigned long long* q =
+        reinterpret_cast<unsigned long long*>(const_cast<float*>(base) + (int64_t)sl * part_stride) + lane;
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+      for (int j = 0; j < RBN; ++j) {
+        a[k][t][j] = __hip_atomic_load(q + (t * 4 + j) * 128, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        b[k][t][j] = __hip_atomic_load(q + (t * 4 + j) * 128 + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+  }
+  f32x4_t own[TN][RBN];
+#pragma unroll
+  for (int t = 0; t < TN; ++t)
+#pragma unroll
+    for (int j = 0; j < RBN; ++j) own[t][j] = acc[t][j];
+  // position p of the sum takes slice p: the own values at p == split, else the fetched slice k = p - (p > split)
+#pragma unroll
+  for (int p = 0; p < S; ++p) {
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+      for (int j = 0; j < RBN; ++j) {
+        const int lo = p > 0 ? p - 1 : 0, hi = p < S - 1 ? p : S - 2;  // the fetched slice is one of a[lo], a[hi]
+        const bool use_lo = p > split;
+        const unsigned long long ua = use_lo ? a[lo][t][j] : a[hi][t][j];
+        const unsigned long long ub = use_lo ? b[lo][t][j] : b[hi][t][j];
+        const f32x4_t other = f32x4_t{__uint_as_float((unsigned)ua), __uint_as_float((unsigned)(ua >> 32)),
+                                      __uint_as_float((unsigned)ub), __uint_as_float((unsigned)(ub >> 32))};
+        const f32x4_t v = p == split ? own[t][j] : other;
+        acc[t][j] = p == 0 ? v : acc[t][j] + v;
+      }
+  }
+}
+
+template <int RBN>
+__device__ inline void sum_slices_keep_own(const float* part, int64_t part_stride, int split, int splits, int NG,
+                                           int ng, int rb0, int rb_lo, int lane, Acc& acc) {
+  if (splits == 2) {
+    sum_other_slices<RBN, 2>(part, part_stride, split, NG, ng, rb0, rb_lo, lane, acc);
+  } else if (splits == 4) {
+    sum_other_slices<RBN, 4>(part, part_stride, split, NG, ng, rb0, rb_lo, lane, acc);
+  } else if (splits == 3) {
+    sum_other_slices<RBN, 3>(part, part_stride, split, NG, ng, rb0, rb_lo, lane, acc);
+  } else {
+    load_slices<RBN>(part, part_stride, splits, NG, ng, rb0, rb_lo, lane, acc);  // all slices, the own one included
+  }
+}
+
 __device__ inline uint2 pack4_f16(float a, float b, float c, float d) {
   return make_uint2((uint32_t)f32_to_f16(a) | ((uint32_t)f32_to_f16(b) << 16),
                     (uint32_t)f32_to_f16(c) | ((uint32_t)f32_to_f16(d) << 16));
@@ -285,12 +359,9 @@ __device__ inline void run_epilogue(const GemmEpilogue& e, int ng, int N, int rb
   }
 }
 
-// Split-K hand-over (splits > 1).  The wavefronts that hold a complete workgroup tile (`owner`) write it as
-// this workgroup's slice; returns true in the workgroup that arrived last for its output tile, which then
-// re-reads all slices in slice order (load_slices, any of its wavefronts) and runs the epilogue.
-__device__ inline bool finish_split(float* part, int64_t part_stride, int split, int splits, int* counters, int NG,
-                                    int ng, int rb0, int lane, bool owner, const Acc& acc, int* s_flag) {
-  if (owner) store_slice(part + (int64_t)split * part_stride, NG, ng, rb0, lane, acc);
+// Split-K hand-over (splits > 1), second part: called by the whole workgroup after its wavefronts have issued their
+// slice stores.  Returns true in the workgroup that arrived last for its output tile.
+__device__ inline bool take_ticket(int splits, int* counters, int* s_flag) {
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): this wavefront's slice stores have completed
   DED_STAMP(4)
   __syncthreads();
@@ -304,6 +375,15 @@ __device__ inline bool finish_split(float* part, int64_t part_stride, int split,
   __syncthreads();
   DED_STAMP(5)
   return *s_flag != 0;
+}
+
+// Hand-over of whole tiles: the wavefronts that hold a complete workgroup tile (`owner`) write it as this
+// workgroup's slice; the last-arriving workgroup then re-reads all slices in slice order (load_slices, any of its
+// wavefronts) and runs the epilogue.
+__device__ inline bool finish_split(float* part, int64_t part_stride, int split, int splits, int* counters, int NG,
+                                    int ng, int rb0, int lane, bool owner, const Acc& acc, int* s_flag) {
+  if (owner) store_slice(part + (int64_t)split * part_stride, NG, ng, rb0, lane, acc);
+  return take_ticket(splits, counters, s_flag);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -609,40 +689,44 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   }
   DED_STAMP(2)
   ssq_publish(epi, rb0, lane, threadIdx.x >> 6, 2 * NWN, ssq, s_ssq);
-  // second half -> LDS -> first half adds
+  // the halves are added through LDS: half h ends up with row blocks 2h, 2h + 1 of its feature group, in
+  // acc[t][0..1]; each half hands the other the two row blocks it does not finish
   __syncthreads();
-  float4* red = reinterpret_cast<float4*>(lds) + wn * ACC_U4 + lane;
-  if (half == 1) {
+  {
+    constexpr int HALF_U4 = TN * 2 * 64;  // two row blocks of one wavefront's accumulators
+    float4* out = reinterpret_cast<float4*>(lds) + (half * NWN + wn) * HALF_U4 + lane;
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        f32x4_t v = acc[t][rb];
-        red[(t * 4 + rb) * 64] = make_float4(v[0], v[1], v[2], v[3]);
+      for (int j = 0; j < 2; ++j) {
+        const f32x4_t v = half == 0 ? acc[t][2 + j] : acc[t][j];
+        out[(t * 2 + j) * 64] = make_float4(v[0], v[1], v[2], v[3]);
       }
-  }
-  __syncthreads();
-  if (half == 0) {
+    __syncthreads();
+    const float4* in = reinterpret_cast<const float4*>(lds) + ((1 - half) * NWN + wn) * HALF_U4 + lane;
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        float4 v = red[(t * 4 + rb) * 64];
-        acc[t][rb] += f32x4_t{v.x, v.y, v.z, v.w};
+      for (int j = 0; j < 2; ++j) {
+        const float4 v = in[(t * 2 + j) * 64];
+        const f32x4_t mine = half == 0 ? acc[t][j] : acc[t][2 + j];
+        acc[t][j] = mine + f32x4_t{v.x, v.y, v.z, v.w};
       }
   }
   DED_STAMP(3)
   const float row_scale = ssq_scale(epi, lane, 2 * NWN, s_ssq);
   const bool store_ok = ng_raw < NG;
   if (splits == 1) {
-    if (half == 0 && store_ok) run_epilogue<EPI, 4>(epi, ng, N, rb0, rb0, row_scale, lane, acc);
-  } else if (finish_split(part, part_stride, split, splits, counters, NG, ng, rb0, lane, half == 0 && store_ok, acc,
-                          &s_flag) &&
-             store_ok) {
-    // both halves take part: wavefront (half, wn) finishes row blocks 2 * half, 2 * half + 1 of feature group wn
-    load_slices<2>(part, part_stride, splits, NG, ng, rb0, half * 2, lane, acc);
-    DED_STAMP(6)
-    run_epilogue<EPI, 2>(epi, ng, N, rb0, rb0 + half * 2, row_scale, lane, acc);
+    if (store_ok) run_epilogue<EPI, 2>(epi, ng, N, rb0, rb0 + half * 2, row_scale, lane, acc);
+  } else {
+    // every wavefront writes the two row blocks it holds; in the last workgroup it fetches the same two row
+    // blocks of the other slices and finishes them
+    if (store_ok) store_slice_rows<2>(part + (int64_t)split * part_stride, NG, ng, rb0, half * 2, lane, acc);
+    if (take_ticket(splits, counters, &s_flag) && store_ok) {
+      sum_slices_keep_own<2>(part, part_stride, split, splits, NG, ng, rb0, half * 2, lane, acc);
+      DED_STAMP(6)
+      run_epilogue<EPI, 2>(epi, ng, N, rb0, rb0 + half * 2, row_scale, lane, acc);
+    }
   }
   DED_STAMP(7)
 }
