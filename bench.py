@@ -31,12 +31,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
 PMC_FETCH_FACTOR = 2.0
 PMC_WRITE_FACTOR = 1.0
 PMC_KIB = {  # class: (FETCH_SIZE, WRITE_SIZE) mean per launch
-    "gemm_qkv": (59748.0, 14346.0),
-    "gemm_o": (21076.0, 6282.0),
-    "gemm_gate_up": (97845.0, 12395.0),
-    "gemm_down": (52181.0, 6282.0),
-    "gemm_lm_head": (140277.0, 24013.0),
-    "tree_attention_c2": (37500.0, 16640.0),
+    "gemm_qkv": (58235.0, 14346.0),
+    "gemm_o": (21083.0, 6282.0),
+    "gemm_gate_up": (95108.0, 12395.0),
+    "gemm_down": (52187.0, 6282.0),
+    "gemm_lm_head": (136289.0, 24012.0),
+    "tree_attention_c2": (37473.0, 16640.0),
 }
 
 
