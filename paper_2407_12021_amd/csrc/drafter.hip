@@ -48,6 +48,7 @@ struct SearchNode {
 
 struct ded_trigram {
   std::unordered_map<uint64_t, int32_t> count_index, index;  // pair -> row
+  std::unordered_map<uint64_t, int32_t> count_pos;           // (count row, word) -> position in that row
   std::vector<uint64_t> count_key;                             // rows in order of first appearance
   std::vector<CountRow> counts;
   std::vector<std::vector<Successor>> rows;
@@ -77,13 +78,14 @@ extern "C" int ded_trigram_count(ded_trigram* m, const int32_t* tokens, int64_t 
         m->count_key.push_back(key);
       }
       CountRow& r = m->counts[(size_t)it->second];
-      size_t j = 0;
-      while (j < r.word.size() && r.word[j] != tokens[i]) ++j;
-      if (j == r.word.size()) {
+      // frequent contexts of a real corpus have thousands of successors: look the word up, do not scan the row
+      auto pos = m->count_pos.find(pair_key(it->second, tokens[i]));
+      if (pos == m->count_pos.end()) {
+        pos = m->count_pos.emplace(pair_key(it->second, tokens[i]), (int32_t)r.word.size()).first;
         r.word.push_back(tokens[i]);
         r.count.push_back(0);
       }
-      r.count[j] += times;
+      r.count[(size_t)pos->second] += times;
       r.total += times;
     }
   } catch (const std::bad_alloc&) {
