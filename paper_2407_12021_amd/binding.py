@@ -60,6 +60,13 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch ships its own HIP runtime.  It has to be in the process before this library is, so that both use
+        # the same one; loaded the other way round, device pointers allocated by torch are unknown to the runtime
+        # this library would have pulled in, and every call that takes one fails.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         i32p, vp = C.POINTER(C.c_int32), C.c_void_p
         L.ded_workspace_bytes.restype = C.c_size_t
