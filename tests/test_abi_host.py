@@ -152,3 +152,16 @@ def test_sample_rejects_null_context():
     from paper_2407_12021_amd import binding as B
     u = (C.c_float * 4)()
     assert B.lib().ded_sample(None, 1.0, 0.9, u) == B.DED_EINVAL
+
+
+def test_library_is_loaded_after_torch():
+    """torch brings its own HIP runtime; the library has to find that one already in the process (loaded the
+    other way round, device pointers allocated by torch are foreign to the runtime the library pulls in).
+    A host-only call must therefore not be able to load the library before torch."""
+    import subprocess
+    import sys
+    code = ("import sys; from paper_2407_12021_amd import binding as B; assert 'torch' not in sys.modules; "
+            "rc, parent, token, end = B.ded_build_tree(7, [[1, 2]], 8); assert rc == 0 and len(parent) == 3; "
+            "assert 'torch' in sys.modules")
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
