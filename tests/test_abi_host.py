@@ -154,7 +154,7 @@ def test_sample_rejects_null_context():
     assert B.lib().ded_sample(None, 1.0, 0.9, u) == B.DED_EINVAL
 
 
-def test_library_is_loaded_after_torch():
+def test_library_is_loaded_after_torch(b):
     """torch brings its own HIP runtime; the library has to find that one already in the process (loaded the
     other way round, device pointers allocated by torch are foreign to the runtime the library pulls in).
     A host-only call must therefore not be able to load the library before torch."""
