@@ -165,3 +165,18 @@ def test_library_is_loaded_after_torch(b):
             "assert 'torch' in sys.modules")
     r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stderr[-2000:]
+
+
+def test_host_api_from_plain_c(b, tmp_path):
+    """tests/c/host_api.c, compiled with gcc against include/ded_verify.h and linked to the shared library, drives
+    the host-only entry points (draft maker, pseudo-sequence, validation) without Python in between."""
+    import subprocess
+    exe = str(tmp_path / "host_api")
+    lib_dir = os.path.dirname(b.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c", "host_api.c"), "-o", exe, "-L", lib_dir, "-lded_verify",
+           "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib", "-L", "/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-3000:]
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.stdout[-2000:], r.stderr[-2000:])
