@@ -113,6 +113,42 @@ def test_small_model_trees_and_edge_cases(dtype):
         v.close()
 
 
+def test_random_shapes_prefixes_and_trees():
+    """60 seeded random cases over model shape (0-3 layers, widths, head counts with grouped-query ratios 1 / 2 / 4,
+    FFN widths, vocabularies that are not multiples of 64), prefix length (0, 1, around the 64-key tile edge, 200),
+    node budget and tree size (1 .. 100 nodes, two mask words): each a full check_step against the oracle."""
+    g = np.random.default_rng(20240717)
+    worst = {"fp32": 0.0, "bf16": 0.0}
+    for case in range(60):
+        dtype = "bf16" if case % 2 else "fp32"
+        Hkv = int(g.choice([1, 2, 3]))
+        H = Hkv * int(g.choice([1, 2, 4]))
+        if dtype == "bf16":
+            hd, d, F, V = 128, int(g.choice([128, 256, 384])), int(g.choice([128, 384, 640])), int(g.choice([496, 512, 1008, 2064]))
+        else:
+            hd, d, F, V = int(g.choice([16, 32, 64, 128])), int(g.choice([48, 64, 96, 200])), int(g.choice([40, 96, 136])), int(g.choice([97, 500, 1000]))
+        L = int(g.choice([0, 1, 2, 3]))
+        max_nodes = int(g.choice([1, 5, 16, 33, 64, 100]))
+        P = int(g.choice([0, 1, 7, 63, 64, 65, 130, 200]))
+        n = int(g.integers(1, max_nodes + 1))
+        cfg = di.ModelConfig(f"rnd{case}", L, d, H, Hkv, hd, F, V, dtype=dtype)
+        w = di.make_weights(cfg, seed=100 + case, gain_jitter=0.1, std=0.04)
+        prefix = di.zipf_tokens(V, P, seed=200 + case) if P else np.zeros(0, np.int32)
+        parent = di.random_tree(n, None, seed=300 + case)
+        token = di.zipf_tokens(V, n, seed=400 + case)
+        print(f"case {case}: {dtype} L{L} d{d} H{H}/{Hkv} hd{hd} F{F} V{V} P{P} n{n}/{max_nodes}", flush=True)
+        ver = _verifier(cfg, w, max_batch=1, kv_capacity=((P + max_nodes + 63) // 64) * 64, max_nodes=max_nodes)
+        pk = pv = None
+        if P:
+            gpu_prefill(ver, [prefix])
+            if L:
+                _, pk, pv = oracle.prefill(cfg, w, prefix)
+        err, _ = check_step(cfg, w, ver, prefix, parent, token, pk, pv)
+        worst[dtype] = max(worst[dtype], err)
+        ver.close()
+    print(f"worst logit error: fp32 {worst['fp32']:.2e}, bf16 {worst['bf16']:.2e}")
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_batch_of_independent_trees(dtype):
     """Independent tree, prefix length and node count per sequence; no cross-sequence attention."""
