@@ -178,6 +178,59 @@ def test_batch_of_independent_trees(dtype):
     ver.close()
 
 
+def test_random_ragged_batches():
+    """40 seeded random batches (2 / 3 / 5 sequences) with ragged prefix lengths and tree sizes: logits, decisions,
+    walk, new prefix length and the compacted cache of every layer against the oracle, sequence by sequence."""
+    g = np.random.default_rng(77)
+    for case in range(40):
+        dtype = "bf16" if case % 2 else "fp32"
+        Hkv = int(g.choice([1, 2]))
+        H = Hkv * int(g.choice([1, 2, 4]))
+        if dtype == "bf16":
+            hd, d, F, V = 128, int(g.choice([128, 256])), int(g.choice([128, 384])), int(g.choice([496, 512, 1008]))
+        else:
+            hd, d, F, V = int(g.choice([16, 64])), int(g.choice([48, 96])), int(g.choice([40, 136])), int(g.choice([97, 500]))
+        L = int(g.choice([1, 2]))
+        B = int(g.choice([2, 3, 5]))
+        max_nodes = int(g.choice([4, 16, 40, 70]))
+        Pc = int(g.choice([0, 7, 64, 130]))  # common part of the prefixes; each sequence then gets 1..16 tokens more
+        ext = [int(g.integers(1, min(16, max_nodes) + 1)) for _ in range(B)]
+        nn = [int(g.integers(1, max_nodes + 1)) for _ in range(B)]
+        cfg = di.ModelConfig(f"rb{case}", L, d, H, Hkv, hd, F, V, dtype=dtype)
+        w = di.make_weights(cfg, seed=500 + case, gain_jitter=0.1, std=0.04)
+        prefixes = [di.zipf_tokens(V, Pc + ext[b], seed=600 + case, stream=b) for b in range(B)]
+        print(f"case {case}: {dtype} L{L} d{d} H{H}/{Hkv} hd{hd} F{F} V{V} B{B} Pc{Pc} ext{ext} n{nn}/{max_nodes}", flush=True)
+        ver = _verifier(cfg, w, max_batch=B, kv_capacity=((Pc + 16 + max_nodes + 63) // 64) * 64, max_nodes=max_nodes)
+        if Pc:
+            gpu_prefill(ver, [p[:Pc] for p in prefixes], seq_count=B)
+        ver.verify_step([Pc] * B, [di.chain_tree(e) for e in ext], [prefixes[b][Pc:] for b in range(B)])
+        _, _, newp = ver.accept(mode=1)
+        plens = [Pc + e for e in ext]
+        assert newp == plens
+        parents = [di.random_tree(n, None, seed=700 + case + b) for b, n in enumerate(nn)]
+        tokens = [di.zipf_tokens(V, n, seed=800 + case, stream=b) for b, n in enumerate(nn)]
+        logits = ver.verify_step(plens, parents, tokens, want_logits=True).cpu().numpy()
+        a_gpu, _ = ver.get_argmax()
+        acc, path, newp = ver.accept(mode=0)
+        for b in range(B):
+            _, pk, pv = oracle.prefill(cfg, w, prefixes[b])
+            ref, kr, vr = oracle.verify_tree(cfg, w, parents[b], tokens[b], pk, pv)
+            assert np.abs(logits[b, : nn[b]] - ref).max() <= TOL[dtype]
+            a_ref, margin = oracle.argmax_margin(ref)
+            sure = margin > MARGIN
+            assert (a_gpu[b, : nn[b]][sure] == a_ref[sure]).all()
+            acc2, path2 = oracle.accept_walk(parents[b], tokens[b], a_gpu[b, : nn[b]])
+            assert acc[b] == acc2 and path[b] == path2 and newp[b] == plens[b] + len(path2)
+            for l in range(L):
+                k_gpu, v_gpu = ver.kv_load(l, b, 0, newp[b])
+                k_ref = oracle.compact_rows(pk[l], kr[l], path[b])
+                v_ref = oracle.compact_rows(pv[l], vr[l], path[b])
+                scale = max(1.0, np.abs(k_ref).max(), np.abs(v_ref).max())
+                assert np.abs(k_gpu.float().cpu().numpy().transpose(1, 0, 2) - k_ref).max() <= TOL[dtype] * scale
+                assert np.abs(v_gpu.float().cpu().numpy().transpose(1, 0, 2) - v_ref).max() <= TOL[dtype] * scale
+        ver.close()
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_lossless_multi_step_decode(dtype):
     """Sec. 2.4: draft-verification decoding reproduces plain greedy autoregressive decoding.
