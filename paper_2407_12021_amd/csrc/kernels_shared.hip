@@ -149,7 +149,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_top_p_kernel(const floa
                                                                       int32_t* __restrict__ token_out) {
   __shared__ float sh[SAMPLE_THREADS / 64];
   __shared__ uint32_t sh_k[2 * (SAMPLE_THREADS / 64)];
-  __shared__ int sh_pick, sh_last;
+  __shared__ int sh_owner;
   const float* row = logits + (int64_t)blockIdx.x * row_stride;
   const int tid = threadIdx.x;
   // pass 1: extreme keys
@@ -205,30 +205,30 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_top_p_kernel(const floa
       last_kept = i;
     }
   }
-  if (tid == 0) {
-    sh_pick = 0x7fffffff;
-    sh_last = -1;
-  }
+  if (tid == 0) sh_owner = -1;
   float total;
-  const float before = block_exclusive_scan(own, sh, total);  // its barriers also publish sh_pick / sh_last
-  if (last_kept >= 0) atomicMax(&sh_last, last_kept);
+  const float before = block_exclusive_scan(own, sh, total);  // its barriers also publish sh_owner
   const float target = uniform[blockIdx.x] * total;
-  if (own > 0.f && before <= target) {
+  // The chunk that holds the target is the last one that starts at or below it (`before` never decreases with
+  // the thread index).  Its thread takes the first id whose running sum passes the target - or, when its own
+  // running sum (rounded in another order than the scan) stops short of it, the chunk's last nucleus id.
+  if (own > 0.f && before <= target) atomicMax(&sh_owner, tid);
+  __syncthreads();
+  if (tid == sh_owner) {
     float run = before;
+    int pick = last_kept;
     for (int i = i0; i < i1; ++i) {
       const float l = row[i];
       if (ordered_key(l) >= lo) {
         run += __expf((l - m) * inv_temp);
         if (run > target) {
-          atomicMin(&sh_pick, i);
+          pick = i;
           break;
         }
       }
     }
+    token_out[blockIdx.x] = pick;
   }
-  __syncthreads();
-  // if rounding left the target at or above the total nobody picked: take the last id of the nucleus
-  if (tid == 0) token_out[blockIdx.x] = sh_pick != 0x7fffffff ? sh_pick : sh_last;
 }
 
 // Same sampler for vocabularies that fit LDS: the weights exp((l - max) / T) are computed once and kept in LDS
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_top_p_lds_kernel(const 
                                                                           int32_t* __restrict__ token_out) {
   __shared__ float e[SAMPLE_LDS_V];
   __shared__ float sh[SAMPLE_THREADS / 64];
-  __shared__ int sh_pick, sh_last;
+  __shared__ int sh_owner;
   const float* row = logits + (int64_t)blockIdx.x * row_stride;
   const int tid = threadIdx.x;
   float m = -INFINITY;
@@ -314,29 +314,28 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_top_p_lds_kernel(const 
       last_kept = i;
     }
   }
-  if (tid == 0) {
-    sh_pick = 0x7fffffff;
-    sh_last = -1;
-  }
+  if (tid == 0) sh_owner = -1;
   float total;
-  const float before = block_exclusive_scan(own, sh, total);  // its barriers also publish sh_pick / sh_last
-  if (last_kept >= 0) atomicMax(&sh_last, last_kept);
+  const float before = block_exclusive_scan(own, sh, total);  // its barriers also publish sh_owner
   const float target = uniform[blockIdx.x] * total;
-  if (own > 0.f && before <= target) {
+  // as in sample_top_p_kernel: the last chunk that starts at or below the target holds it
+  if (own > 0.f && before <= target) atomicMax(&sh_owner, tid);
+  __syncthreads();
+  if (tid == sh_owner) {
     float run = before;
+    int pick = last_kept;
     for (int i = i0; i < i1; ++i) {
       const float w = e[i];
       if (__float_as_uint(w) >= lo) {
         run += w;
         if (run > target) {
-          atomicMin(&sh_pick, i);
+          pick = i;
           break;
         }
       }
     }
+    token_out[blockIdx.x] = pick;
   }
-  __syncthreads();
-  if (tid == 0) token_out[blockIdx.x] = sh_pick != 0x7fffffff ? sh_pick : sh_last;
 }
 
 void launch_sample_top_p(const float* logits, int64_t row_stride, int rows, int V, float temperature, float top_p,

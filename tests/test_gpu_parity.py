@@ -468,6 +468,26 @@ def test_stochastic_approval(dtype):
     ver.close()
 
 
+def test_sampler_when_the_running_sum_stops_short_of_the_target():
+    """A case a random sweep found: a flat distribution over 36880 tokens (just above what the LDS-resident kernel
+    holds) at T = 2.9, top-p 0.9, where for one node the scan places the target in a thread's chunk but that
+    thread's own running sum, rounded in another order, ends just below it.  The token must still come from that
+    chunk (an earlier version fell back to the last id of the whole nucleus)."""
+    V = 36880
+    cfg = di.ModelConfig("samp-edge", 1, 256, 2, 2, 128, 128, V, dtype="bf16")
+    w = di.make_weights(cfg, seed=929, gain_jitter=0.1, std=0.1)
+    nn = [28, 32]
+    ver = _verifier(cfg, w, max_batch=2, kv_capacity=128, max_nodes=40)
+    parents = [di.random_tree(n, None, seed=58 + b) for b, n in enumerate(nn)]
+    tokens = [di.zipf_tokens(V, n, seed=79, stream=b) for b, n in enumerate(nn)]
+    logits = ver.verify_step([0, 0], parents, tokens, want_logits=True).cpu().numpy()
+    combos = [(0.2571029967541381, 1.0), (0.341189999444725, 0.5), (1.7843192694332748, 0.01), (2.909550738650948, 0.9)]
+    exact, loose, _ = _check_sampling(ver, logits, parents, tokens, combos, seed=29)
+    assert exact + loose == 4 * sum(nn)
+    ver.accept(mode=0)
+    ver.close()
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_maximum_tree_size_and_full_cache(dtype):
     """256 nodes (all four ancestor-mask words), once as a random tree and once as one 256-deep chain, with the
