@@ -231,6 +231,77 @@ def test_random_ragged_batches():
         ver.close()
 
 
+def test_random_planted_trees_over_three_steps():
+    """30 seeded random cases, three steps each: random branched trees in which, level by level, a random subset of
+    nodes is given the model's own token of its parent (so the walk goes several levels deep and has to choose among
+    branches), verified, accepted and compacted; the next step runs on the compacted cache.  The oracle sees token ids
+    only (its own prefill of everything committed so far): logits relative to their scale, the walk bit for bit on the
+    GPU's tokens (and on the oracle's where margins allow), new prefix length, and every layer's cache rows."""
+    g = np.random.default_rng(4242)
+    lengths = {}
+    for case in range(30):
+        dtype = "bf16" if case % 2 else "fp32"
+        Hkv = int(g.choice([1, 2]))
+        H = Hkv * int(g.choice([1, 2]))
+        if dtype == "bf16":
+            hd, d, F, V = 128, int(g.choice([128, 256])), int(g.choice([128, 384])), int(g.choice([496, 512]))
+        else:
+            hd, d, F, V = int(g.choice([16, 64])), int(g.choice([48, 96])), int(g.choice([40, 136])), int(g.choice([97, 500]))
+        L = int(g.choice([1, 2, 3]))
+        max_nodes = int(g.choice([8, 24, 64, 90]))
+        P0 = int(g.choice([0, 3, 60, 64, 129]))
+        cfg = di.ModelConfig(f"pl{case}", L, d, H, Hkv, hd, F, V, dtype=dtype)
+        w = di.make_weights(cfg, seed=1500 + case, gain_jitter=0.1, std=0.15)  # wide top-1 margins
+        seq = di.zipf_tokens(V, P0 + 1, seed=1600 + case).tolist()  # committed tokens; the last one is the root
+        print(f"case {case}: {dtype} L{L} d{d} H{H}/{Hkv} hd{hd} F{F} V{V} P0 {P0} max_nodes {max_nodes}", flush=True)
+        ver = _verifier(cfg, w, max_batch=1, kv_capacity=((P0 + 4 * max_nodes + 63) // 64) * 64 + 64, max_nodes=max_nodes)
+        if P0:
+            gpu_prefill(ver, [np.array(seq[:P0], np.int32)])
+        P = P0
+        for step in range(3):
+            n = int(g.integers(1, max_nodes + 1))
+            parent = di.random_tree(n, None, seed=1700 + 10 * case + step)
+            depth = oracle.node_depths(parent)
+            token = di.zipf_tokens(V, n, seed=1800 + 10 * case + step).copy()
+            token[0] = seq[-1]
+            for lvl in range(1, int(depth.max()) + 1 if n > 1 else 1):
+                ver.verify_step([P], [parent], [token])
+                a, _ = ver.get_argmax()
+                for i in np.flatnonzero(depth == lvl):
+                    taken = any(parent[j] == parent[i] and j < i and token[j] == a[0, parent[i]] for j in range(n))
+                    if g.random() < 0.6 and not taken:
+                        token[i] = a[0, parent[i]]
+            pk = pv = None
+            if P:
+                _, pk, pv = oracle.prefill(cfg, w, np.array(seq[:P], np.int32))
+            ref, kr, vr = oracle.verify_tree(cfg, w, parent, token, pk, pv)
+            logits = ver.verify_step([P], [parent], [token], want_logits=True)[0, :n].cpu().numpy().astype(np.float64)
+            err = np.abs(logits - ref).max()
+            assert err <= (1e-4 if dtype == "fp32" else 1e-2) * max(1.0, np.abs(ref).max()), (err, np.abs(ref).max())
+            a_gpu, _ = ver.get_argmax()
+            acc, path, newp = ver.accept(mode=0)
+            acc2, path2 = oracle.accept_walk(parent, token, a_gpu[0, :n])
+            assert acc[0] == acc2 and path[0] == path2 and newp[0] == P + len(path2)
+            lengths[len(path2)] = lengths.get(len(path2), 0) + 1
+            a_ref, margin = oracle.argmax_margin(ref)
+            acc3, path3 = oracle.accept_walk(parent, token, a_ref)
+            if all(margin[v] > MARGIN for v in set(path2) | set(path3)):
+                assert acc2 == acc3 and path2 == path3
+            for l in range(L):
+                k_gpu, v_gpu = ver.kv_load(l, 0, 0, newp[0])
+                k_ref = oracle.compact_rows(pk[l] if P else kr[l][:0], kr[l], path2)
+                v_ref = oracle.compact_rows(pv[l] if P else vr[l][:0], vr[l], path2)
+                scale = max(1.0, np.abs(k_ref).max(), np.abs(v_ref).max())
+                assert np.abs(k_gpu.float().cpu().numpy().transpose(1, 0, 2) - k_ref).max() <= 2 * TOL[dtype] * scale
+                assert np.abs(v_gpu.float().cpu().numpy().transpose(1, 0, 2) - v_ref).max() <= 2 * TOL[dtype] * scale
+            seq = seq[:P] + [int(token[v]) for v in path2] + [int(acc2[-1])]
+            P = newp[0]
+            assert len(seq) == P + 1
+        ver.close()
+    print(f"accepted path lengths: {dict(sorted(lengths.items()))}")
+    assert sum(c for k, c in lengths.items() if k >= 3) >= 20  # the walks did go deep
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_lossless_multi_step_decode(dtype):
     """Sec. 2.4: draft-verification decoding reproduces plain greedy autoregressive decoding.
