@@ -113,6 +113,44 @@ def test_small_model_trees_and_edge_cases(dtype):
         v.close()
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_errors_leave_the_context_usable(dtype):
+    """Every rejected call returns its documented code before anything is launched, and the step after the
+    errors is as correct as any other."""
+    from paper_2407_12021_amd import binding as B
+    hd = 128 if dtype == "bf16" else 32
+    cfg = di.ModelConfig("err-" + dtype, 2, 128, 2, 2, hd, 256, 512, dtype=dtype)
+    w = di.make_weights(cfg, seed=3, gain_jitter=0.1, std=0.05)
+    ver = _verifier(cfg, w, max_batch=2, kv_capacity=128, max_nodes=16)
+    prefix = di.zipf_tokens(512, 20, seed=1)
+    gpu_prefill(ver, [prefix])
+    _, pk, pv = oracle.prefill(cfg, w, prefix)
+    parent = di.random_tree(12, None, seed=2)
+    token = di.zipf_tokens(512, 12, seed=3)
+
+    def code(fn):
+        try:
+            fn()
+            return B.DED_OK
+        except B.DedError as e:
+            return e.code
+
+    bad_parent = parent.copy()
+    bad_parent[5] = 7  # a parent that comes after its child
+    bad_token = token.copy()
+    bad_token[3] = 512  # outside the vocabulary
+    assert code(lambda: ver.verify_step([20], [bad_parent], [token])) == B.DED_ETREE
+    assert code(lambda: ver.verify_step([20], [parent], [bad_token])) == B.DED_ETOKEN
+    assert code(lambda: ver.verify_step([120], [parent], [token])) == B.DED_ECAP
+    assert code(lambda: ver.verify_step([20] * 3, [parent] * 3, [token] * 3)) == B.DED_EINVAL  # above max_batch
+    assert code(lambda: ver.accept(mode=0)) == B.DED_ESTATE  # nothing pending
+    check_step(cfg, w, ver, prefix, parent, token, pk, pv)
+    ver.verify_step([21], [parent], [token])
+    assert code(lambda: ver.accept(mode=1)) == B.DED_ETREE  # forced acceptance needs a chain
+    ver.accept(mode=0)
+    ver.close()
+
+
 def test_random_shapes_prefixes_and_trees():
     """60 seeded random cases over model shape (0-3 layers, widths, head counts with grouped-query ratios 1 / 2 / 4,
     FFN widths, vocabularies that are not multiples of 64), prefix length (0, 1, around the 64-key tile edge, 200),
