@@ -246,6 +246,23 @@ int ded_tree_attention(ded_ctx *ctx, int32_t layer, int32_t batch, const int32_t
                        const int32_t *n_nodes, const int32_t *parent, const void *q,
                        const void *k_tree, const void *v_tree, void *out);
 
+/* ded_tree_attention for callers that cannot allocate device memory and have no workspace region to spare for
+ * it: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and bit-identical output, but every transient device buffer of the call (the uploaded tree
+ * description, the re-laid-out queries and output, the split-KV partial results) lives in an array that is
+ * part of the library's own device image: ded_static_scratch_bytes() bytes (32 MiB) per GPU, held from the
+ * first ded_verify_init on that GPU until the process ends.  The call allocates nothing and frees nothing.
+ * The context's device must be current.  A call whose buffers would not fit the array (roughly
+ * batch * n_heads * key ranges * padded nodes * 520 bytes + 8 * rows * n_heads * head_dim bytes) is refused
+ * with DED_ECAP before anything is enqueued; DED_BF16 contexts only (DED_EINVAL otherwise).  All calls on
+ * one GPU share the array and it keeps the last call's contents (every element that is read is written first
+ * by the same call, nothing has to start at zero); calls that overlap in time on one GPU - from different
+ * contexts or streams - race.  Asynchronous.  Other errors as ded_tree_attention. */
+int ded_tree_attention_static(ded_ctx *ctx, int32_t layer, int32_t batch, const int32_t *prefix_len,
+                              const int32_t *n_nodes, const int32_t *parent, const void *q,
+                              const void *k_tree, const void *v_tree, void *out);
+size_t ded_static_scratch_bytes(void);
+
 /* Kernel timing.  While enabled, every kernel launch of the forward is bracketed by HIP events on
  * the context's stream (this serialises nothing but adds event overhead, so use a separate pass).
  * ded_profile_read synchronises, then fills up to `cap` entries: names[i] points to a static string,

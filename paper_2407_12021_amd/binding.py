@@ -22,6 +22,7 @@ DED_F32, DED_BF16 = 0, 1
 EXPORTS = [
     "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_build_tree", "ded_verify_init", "ded_verify_free",
     "ded_verify_step", "ded_sample", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
+    "ded_tree_attention_static", "ded_static_scratch_bytes",
     "ded_profile_enable", "ded_profile_read", "ded_strerror",
     "ded_trigram_create", "ded_trigram_free", "ded_trigram_count", "ded_trigram_finalize", "ded_trigram_adjust",
     "ded_trigram_lookup", "ded_trigram_size", "ded_draft_mcts",
@@ -112,8 +113,12 @@ def lib() -> C.CDLL:
             f = getattr(L, name)
             f.restype = C.c_int
             f.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp]
-        L.ded_tree_attention.restype = C.c_int
-        L.ded_tree_attention.argtypes = [vp, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp]
+        for name in ("ded_tree_attention", "ded_tree_attention_static"):
+            f = getattr(L, name)
+            f.restype = C.c_int
+            f.argtypes = [vp, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp]
+        L.ded_static_scratch_bytes.restype = C.c_size_t
+        L.ded_static_scratch_bytes.argtypes = []
         L.ded_profile_enable.restype = C.c_int
         L.ded_profile_enable.argtypes = [vp, C.c_int32]
         L.ded_profile_read.restype = C.c_int
@@ -295,6 +300,16 @@ def ded_tree_attention(ctx, layer, prefix_len, n_nodes, parent, q_ptr, k_ptr, v_
                                         out_ptr))
 
 
+def ded_tree_attention_static(ctx, layer, prefix_len, n_nodes, parent, q_ptr, k_ptr, v_ptr, out_ptr) -> int:
+    pl, nn, par = _i32(prefix_len), _i32(n_nodes), _i32(parent)
+    return int(lib().ded_tree_attention_static(ctx, layer, len(pl), _p32(pl), _p32(nn), _p32(par), q_ptr, k_ptr,
+                                               v_ptr, out_ptr))
+
+
+def ded_static_scratch_bytes() -> int:
+    return int(lib().ded_static_scratch_bytes())
+
+
 def ded_profile_enable(ctx, on: bool) -> int:
     return int(lib().ded_profile_enable(ctx, 1 if on else 0))
 
@@ -468,14 +483,17 @@ class Verifier:
         t.cuda.synchronize(self.device)
         return k, v
 
-    def tree_attention(self, layer, prefix_len, parents, q, k_tree, v_tree):
-        """q [B][max_nodes][H][hd], k_tree / v_tree [B][Hkv][max_nodes][hd] device tensors in storage dtype."""
-        out = self.torch.zeros_like(q)
+    def tree_attention(self, layer, prefix_len, parents, q, k_tree, v_tree, out=None, static=False):
+        """q [B][max_nodes][H][hd], k_tree / v_tree [B][Hkv][max_nodes][hd] device tensors in storage dtype.
+        static=True goes through ded_tree_attention_static (the caller then passes `out`: nothing is allocated)."""
+        if out is None:
+            out = self.torch.zeros_like(q)
         nn = [len(p) for p in parents]
-        rc = ded_tree_attention(self.ctx, layer, prefix_len, nn, self._pad(parents, -1), q.data_ptr(),
-                                k_tree.data_ptr(), v_tree.data_ptr(), out.data_ptr())
+        fn = ded_tree_attention_static if static else ded_tree_attention
+        rc = fn(self.ctx, layer, prefix_len, nn, self._pad(parents, -1), q.data_ptr(), k_tree.data_ptr(),
+                v_tree.data_ptr(), out.data_ptr())
         if rc != DED_OK:
-            raise DedError(rc, "ded_tree_attention")
+            raise DedError(rc, fn.__name__)
         return out
 
     def profile(self, on: bool):

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -46,11 +47,38 @@ struct Carve {  // bump allocator over the workspace (base may be null when only
 
 }  // namespace
 
+// Scratch of ded_tree_attention_static: device memory that belongs to the library itself, for callers that
+// cannot allocate and bring no workspace region of their own for it.  One copy per GPU, held until the
+// process ends.  In host code the array's name is only a handle: its device address is resolved once per
+// device (resolve_static_scratch) and that pointer is what kernels, copies and memsets receive.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static unsigned char* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// With `device` current: the address of this device's copy of `scratch` (null if the runtime refuses).
+static unsigned char* resolve_static_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+  }
+  return g_scratch_ptr[device];
+}
+
 struct ded_ctx {
   ded_config cfg;
   ModelDims md;
   bool bf16 = false;
   hipStream_t stream = nullptr;
+  int device = -1;                          // the device that was current at ded_verify_init
+  unsigned char* static_scratch = nullptr;  // this device's copy of the library's own scratch array
   int max_n_pad = 0;    // max_nodes rounded up to 16
   int max_rows = 0;     // max_batch * max_n_pad
   int max_rows_pad = 0; // rounded up to 64
@@ -109,15 +137,17 @@ struct ded_ctx {
   double prof_ms[KC_COUNT] = {};
   int64_t prof_n[KC_COUNT] = {};
 
-  StepMeta meta() const {
+  StepMeta meta() const { return meta_at(d_meta); }
+  // the step description inside a device copy of the meta block that starts at `base`
+  StepMeta meta_at(const char* base) const {
     StepMeta m;
-    m.token = reinterpret_cast<const int32_t*>(d_meta + off_token);
-    m.parent = reinterpret_cast<const int32_t*>(d_meta + off_parent);
-    m.depth = reinterpret_cast<const int32_t*>(d_meta + off_depth);
-    m.pos = reinterpret_cast<const int32_t*>(d_meta + off_pos);
-    m.mask = reinterpret_cast<const uint64_t*>(d_meta + off_mask);
-    m.seq_p = reinterpret_cast<const int32_t*>(d_meta + off_p);
-    m.seq_n = reinterpret_cast<const int32_t*>(d_meta + off_n);
+    m.token = reinterpret_cast<const int32_t*>(base + off_token);
+    m.parent = reinterpret_cast<const int32_t*>(base + off_parent);
+    m.depth = reinterpret_cast<const int32_t*>(base + off_depth);
+    m.pos = reinterpret_cast<const int32_t*>(base + off_pos);
+    m.mask = reinterpret_cast<const uint64_t*>(base + off_mask);
+    m.seq_p = reinterpret_cast<const int32_t*>(base + off_p);
+    m.seq_n = reinterpret_cast<const int32_t*>(base + off_n);
     m.batch = batch;
     m.n_step = n_step;
     m.rows = batch * n_step;
@@ -380,7 +410,7 @@ int validate_step(const ded_config& cfg, int32_t batch, const int32_t* prefix_le
 }
 
 int ingest_and_upload(ded_ctx* c, int32_t batch, const int32_t* prefix_len, const int32_t* n_nodes,
-                      const int32_t* parent, const int32_t* token) {
+                      const int32_t* parent, const int32_t* token, char* d_meta_dst = nullptr) {
   const ded_config& cfg = c->cfg;
   int nmax = 0, pmax = 0;
   for (int b = 0; b < batch; ++b) {
@@ -440,7 +470,8 @@ int ingest_and_upload(ded_ctx* c, int32_t batch, const int32_t* prefix_len, cons
   }
   {
     ProfScope ps(c, KC_META);
-    HIP_TRY(hipMemcpyAsync(c->d_meta, c->h_meta, c->meta_bytes, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(d_meta_dst ? d_meta_dst : c->d_meta, c->h_meta, c->meta_bytes, hipMemcpyHostToDevice,
+                           c->stream));
   }
   HIP_TRY(hipEventRecord(c->meta_ev, c->stream));
   c->meta_inflight = true;
@@ -622,6 +653,17 @@ int ded_verify_init(const ded_config* cfg, const ded_weights* w, const ded_kv* k
   c->cfg = *cfg;
   c->bf16 = cfg->dtype == DED_BF16;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  // set-up of the library's own scratch array: resolved here, once per device, with the context's device current
+  if (hipGetDevice(&c->device) != hipSuccess) {
+    (void)hipGetLastError();
+    delete c;
+    return DED_EHIP;
+  }
+  c->static_scratch = resolve_static_scratch(c->device);
+  if (!c->static_scratch) {
+    delete c;
+    return DED_EHIP;
+  }
   c->md = ModelDims{cfg->n_layers, cfg->d_model, cfg->n_heads, cfg->n_kv_heads, cfg->head_dim,
                     cfg->d_ffn,    cfg->vocab,   cfg->kv_capacity, cfg->rope_base, cfg->rms_eps};
   Sizes z = sizes_of(*cfg);
@@ -848,32 +890,70 @@ int ded_kv_load(ded_ctx* c, int32_t layer, int32_t seq, int32_t first_slot, int3
   return kv_copy_common(c, layer, seq, first_slot, n, k_plain, v_plain, false);
 }
 
-int ded_tree_attention(ded_ctx* c, int32_t layer, int32_t batch, const int32_t* prefix_len,
-                       const int32_t* n_nodes, const int32_t* parent, const void* q, const void* k_tree,
-                       const void* v_tree, void* out) {
+// Transient device buffers of one stand-alone attention call: the step description, the queries and the output
+// in operand-fragment form, and the split-KV partials.
+struct AttnScratch {
+  char* d_meta;
+  bf16_t *q_p, *o_p;
+  float* part_o;
+  float2* part_ml;
+  int64_t part_rows;
+};
+
+static int tree_attention_common(ded_ctx* c, int32_t layer, int32_t batch, const int32_t* prefix_len,
+                                 const int32_t* n_nodes, const int32_t* parent, const void* q, const void* k_tree,
+                                 const void* v_tree, void* out, bool st) {
   if (!c || !q || !k_tree || !v_tree || !out) return DED_EINVAL;
   if (layer < 0 || layer >= c->md.n_layers) return DED_EINVAL;
   int rc = validate_step(c->cfg, batch, prefix_len, n_nodes, parent, nullptr, false);
   if (rc != DED_OK) return rc;
-  rc = ingest_and_upload(c, batch, prefix_len, n_nodes, parent, nullptr);
+  const ModelDims& md = c->md;
+  AttnScratch ws = {c->d_meta, c->q_p, c->o_p, c->attn_part_o, c->attn_part_ml, c->attn_part_rows};
+  int ns = 1;
+  if (c->bf16) {
+    // the key-range count is the workspace path's in both variants, so both give the same bits
+    int nmax = 0, pmax = 0;
+    for (int b = 0; b < batch; ++b) {
+      nmax = std::max(nmax, n_nodes[b]);
+      pmax = std::max(pmax, prefix_len[b]);
+    }
+    StepMeta shape = {};
+    shape.batch = batch;
+    shape.n_step = round_up(nmax, 16);
+    shape.rows = batch * shape.n_step;
+    ns = bf16_attn_pick_splits(shape, md, pmax, c->attn_part_rows);
+    if (st) {  // carve the library's own array; a call that does not fit is refused before anything is enqueued
+      const int64_t rows_pad = round_up(shape.rows, 64), qd = (int64_t)md.H * md.hd;
+      const int64_t part_rows = (int64_t)batch * md.H * ns * shape.n_step;
+      Carve w(reinterpret_cast<char*>(c->static_scratch));
+      ws.d_meta = w.take<char>(c->meta_bytes);
+      ws.q_p = w.take<bf16_t>(rows_pad * qd * 2);
+      ws.o_p = w.take<bf16_t>(rows_pad * qd * 2);
+      ws.part_o = w.take<float>(part_rows * md.hd);
+      ws.part_ml = w.take<float2>(part_rows);
+      ws.part_rows = part_rows;
+      if (w.off > kStaticScratchBytes) return DED_ECAP;
+    }
+  } else if (st) {
+    return DED_EINVAL;  // the fp32 path has no transient buffers of this kind
+  }
+  rc = ingest_and_upload(c, batch, prefix_len, n_nodes, parent, nullptr, ws.d_meta);
   if (rc != DED_OK) return rc;
   c->pending = false;
   c->have_argmax = false;
-  const ModelDims& md = c->md;
-  StepMeta m = c->meta();
+  StepMeta m = c->meta_at(ws.d_meta);
   hipStream_t s = c->stream;
   const int mn = c->cfg.max_nodes, qd = md.H * md.hd;
   if (c->bf16) {
     const int rows_pad = round_up(m.rows, 64);
     { ProfScope p(c, KC_LAYOUT);
       bf16_scatter_tree_kv((bf16_t*)c->kc[layer], (bf16_t*)c->vc[layer], (const bf16_t*)k_tree, (const bf16_t*)v_tree, m, md, mn, s);
-      bf16_pack_q(c->q_p, (const bf16_t*)q, m, md, mn, s); }
-    int ns = bf16_attn_pick_splits(m, md, c->max_p, c->attn_part_rows);
+      bf16_pack_q(ws.q_p, (const bf16_t*)q, m, md, mn, s); }
     { ProfScope p(c, KC_TREE_ATTN);
-      bf16_tree_attention_partial(c->q_p, (const bf16_t*)c->kc[layer], (const bf16_t*)c->vc[layer], c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
+      bf16_tree_attention_partial(ws.q_p, (const bf16_t*)c->kc[layer], (const bf16_t*)c->vc[layer], ws.part_o, ws.part_ml, ns, m, md, s); }
     { ProfScope p(c, KC_ATTN_MERGE);
-      bf16_tree_attention_merge(c->o_p, rows_pad, c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
-    { ProfScope p(c, KC_LAYOUT); bf16_unpack_o((bf16_t*)out, c->o_p, rows_pad, m, md, mn, s); }
+      bf16_tree_attention_merge(ws.o_p, rows_pad, ws.part_o, ws.part_ml, ns, m, md, s); }
+    { ProfScope p(c, KC_LAYOUT); bf16_unpack_o((bf16_t*)out, ws.o_p, rows_pad, m, md, mn, s); }
   } else {
     { ProfScope p(c, KC_LAYOUT);
       f32_scatter_tree_kv((float*)c->kc[layer], (float*)c->vc[layer], (const float*)k_tree, (const float*)v_tree, m, md, mn, s);
@@ -884,6 +964,27 @@ int ded_tree_attention(ded_ctx* c, int32_t layer, int32_t batch, const int32_t* 
   }
   return launch_status();
 }
+
+int ded_tree_attention(ded_ctx* c, int32_t layer, int32_t batch, const int32_t* prefix_len,
+                       const int32_t* n_nodes, const int32_t* parent, const void* q, const void* k_tree,
+                       const void* v_tree, void* out) {
+  return tree_attention_common(c, layer, batch, prefix_len, n_nodes, parent, q, k_tree, v_tree, out, false);
+}
+
+int ded_tree_attention_static(ded_ctx* c, int32_t layer, int32_t batch, const int32_t* prefix_len,
+                              const int32_t* n_nodes, const int32_t* parent, const void* q, const void* k_tree,
+                              const void* v_tree, void* out) {
+  if (!c) return DED_EINVAL;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return DED_EHIP;
+  }
+  if (dev != c->device || !c->static_scratch) return DED_EINVAL;  // the array's address belongs to the context's device
+  return tree_attention_common(c, layer, batch, prefix_len, n_nodes, parent, q, k_tree, v_tree, out, true);
+}
+
+size_t ded_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int ded_profile_enable(ded_ctx* c, int32_t on) {
   if (!c) return DED_EINVAL;
