@@ -155,3 +155,16 @@ def test_c5_shape_short_prefix_without_hand_over():
     """The Llama-3-8B shape (GQA 32 / 8, vocabulary 128256, RoPE base 500000, 256-node trees, batch 8) on
     2048-token prefixes, where the oracle can afford its own pass over the prefix: sequence 5, nothing handed over."""
     _teacher_forced_check("c5", (5,), untaught=(5,), prefix_len=2048)
+
+
+def test_c4_all_40_layers_batch4_teacher_forced():
+    """Config 4 at its own depth: the 13B shape with all 40 layers, prefix 2048, 128-node trees of depth 8, batch 4
+    (ragged); the oracle verifies the tree step of sequences 0 and 3 over all 40 layers from the handed-over
+    prefix K/V.  Bounds: logits 2e-2 absolute, tokens exact above the 0.05 margin, walk and compaction exact."""
+    _teacher_forced_check("c4", (0, 3), layers=di.WORKLOADS["c4"].model.n_layers)
+
+
+def test_c5_all_32_layers_gqa_batch8_teacher_forced():
+    """Config 5 at its own depth: the Llama-3-8B shape with all 32 layers (32 query / 8 KV heads, vocabulary 128256,
+    RoPE base 500000), prefix 16384, 256-node trees of depth 10, batch 8 (ragged); sequences 0 and 7."""
+    _teacher_forced_check("c5", (0, 7), layers=di.WORKLOADS["c5"].model.n_layers)
