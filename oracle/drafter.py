@@ -11,13 +11,14 @@ Readings (the paper is silent or its listing is garbled; each is stated where it
   T2  The threshold t eliminates tri-grams whose count is below t; the survivors keep their Eq. (1) value (no
       re-normalisation).  A context whose tri-grams are all eliminated disappears.
   T3  The successors of a context are kept in order of first appearance (corpus order, then Adjust3Gram insertions).
-  M1  A tree node's `word` is the pair (previous word, word); the root holds the last two tokens of the input.  The
-      words a node may be followed by ("untried words") are the successors of its pair in the tri-gram matrix.
-  M2  Selection walks down while the node has no untried words, has children and the sentence is not full (the text
-      of Appendix G; the listing's condition has a stray negation).  select_child takes the child of highest score
+  M1  A search node stands for a word reached after a given previous word, i.e. for a bigram context; the root is
+      the last two tokens of the input.  The words that may follow a node and have no child yet (`pending`) are
+      the successors of its context in the tri-gram matrix.
+  M2  Selection walks down while the node has no pending words, has children and the sentence is not full (the text
+      of Appendix G; the listing's condition has a stray negation).  The step down takes the child of highest score
       Eq. (2) with Q(s,a) = child.score / child.visits (0 for an unvisited child), P(s,a) = the child's tri-gram
       probability, N(s,a) = child.visits and the sum over the node's children; the first child wins a tie.
-  M3  Expansion creates a child for every untried word at once (as listed), empties the untried list, and
+  M3  Expansion creates a child for every pending word at once (as listed), empties the pending list, and
       continues with the child created last.
   M4  sentence_length = l + 1: the root pair plus l words.
   M5  Simulation draws the next word of the pair last reached by inverse CDF over that pair's successors in their
@@ -29,7 +30,8 @@ Readings (the paper is silent or its listing is garbled; each is stated where it
   M7  Sentences are the root-to-leaf paths of the search tree (leaf = node without children), a sentence's score is
       its leaf's accumulated score; they are sorted by descending score, depth-first order (children in creation
       order) among equals; the first n are returned, the root pair left out.
-  A1  Adjust3Gram: i runs over 2 .. len(subTokens) - 1 (0-based indices; the listing's upper limit is the length).
+  A1  Adjust3Gram: every tri-gram that lies inside the window is updated, i.e. the third-word index runs over
+      2 .. len(window) - 1 (0-based; the listing's upper limit is the length).
       A new tri-gram is appended to its context's successors (a new context is created if needed).
 """
 from __future__ import annotations
@@ -73,17 +75,11 @@ class TriGramMatrix:
         return self.matrix.get((int(ctx[0]), int(ctx[1])), {}).get(int(w), 0.0)
 
     def adjust_3gram(self, tokens: Sequence[int], max_length: int, increment: float, max_prob: float) -> None:
-        """Alg. 2 (A1)."""
-        n = len(tokens)
-        start_index = max(0, n - max_length)
-        sub_tokens = [int(x) for x in tokens[start_index:n]]
-        for i in range(2, len(sub_tokens)):
-            ctx, w = (sub_tokens[i - 2], sub_tokens[i - 1]), sub_tokens[i]
-            row = self.matrix.setdefault(ctx, {})
-            if w in row:
-                row[w] = min(row[w] + increment, max_prob)
-            else:
-                row[w] = increment
+        """Alg. 2 (A1): reinforce every tri-gram inside the last `max_length` tokens."""
+        window = [int(x) for x in tokens[max(0, len(tokens) - max_length):]]
+        for a, b, w in zip(window, window[1:], window[2:]):
+            row = self.matrix.setdefault((a, b), {})
+            row[w] = min(row[w] + increment, max_prob) if w in row else increment
 
 
 def exploration_factor(sum_n: float, c1: float, c2: float) -> float:
@@ -96,95 +92,115 @@ def puct(q: float, p: float, n_sa: float, sum_n: float, c1: float, c2: float) ->
     return q + exploration_factor(sum_n, c1, c2) * p * math.sqrt(sum_n) / (1.0 + n_sa)
 
 
-class Node:
-    def __init__(self, p_word: int, word: int, prior: float, untried_words: List[Tuple[int, float]],
-                 parent: Optional["Node"]) -> None:
-        self.word: Pair = (p_word, word)
-        self.prior = prior                  # P(s,a) of the action that leads here
-        self.untried_words = untried_words  # [(word, probability)]
-        self.children: List[Node] = []
+class SearchNode:
+    """One word of a candidate sentence, reached after `context[0]` (M1)."""
+
+    def __init__(self, context: Pair, prior: float, pending: List[Tuple[int, float]],
+                 parent: Optional["SearchNode"]) -> None:
+        self.context = context    # (previous word, this node's word)
+        self.prior = prior        # P(s,a) of the step that leads here
+        self.pending = pending    # successors of `context` that have no child yet: [(word, probability)]
+        self.children: List[SearchNode] = []
         self.parent = parent
         self.visits = 0
         self.score = 0.0
 
-    def select_child(self, c1: float, c2: float) -> "Node":
-        sum_n = float(sum(ch.visits for ch in self.children))
-        best, best_val = None, None
-        for ch in self.children:
-            q = ch.score / ch.visits if ch.visits > 0 else 0.0
-            val = puct(q, ch.prior, float(ch.visits), sum_n, c1, c2)
-            if best is None or val > best_val:
-                best, best_val = ch, val
-        return best
+    @property
+    def token(self) -> int:
+        return self.context[1]
+
+
+def _best_child(node: SearchNode, c1: float, c2: float) -> SearchNode:
+    """The child of highest Eq. (2) score; the first one among equals (M2)."""
+    sum_n = float(sum(ch.visits for ch in node.children))
+    values = [puct(ch.score / ch.visits if ch.visits > 0 else 0.0, ch.prior, float(ch.visits), sum_n, c1, c2)
+              for ch in node.children]
+    return node.children[values.index(max(values))]
+
+
+def _descend(root: SearchNode, sentence: List[int], full: int, c1: float, c2: float) -> SearchNode:
+    """Selection (M2): follow best children while everything below the node is already expanded; the words passed
+    are appended to `sentence` (a token list that starts with the root's two tokens)."""
+    node = root
+    while not node.pending and node.children and len(sentence) < full:
+        node = _best_child(node, c1, c2)
+        sentence.append(node.token)
+    return node
+
+
+def _expand(matrix: TriGramMatrix, node: SearchNode) -> SearchNode:
+    """Expansion (M3): one child per pending word, in stored order; the search goes on with the last one."""
+    for word, prior in node.pending:
+        ctx = (node.token, word)
+        node.children.append(SearchNode(ctx, prior, matrix.successors(ctx), node))
+    node.pending = []
+    return node.children[-1]
+
+
+def _rollout(matrix: TriGramMatrix, sentence: List[int], full: int, uniform: Sequence[float], base: int) -> None:
+    """Simulation (M5): extend `sentence` to `full` tokens by inverse-CDF draws; the draw that adds the j-th word
+    after the root pair (j counted from 0) uses uniform[base + j]."""
+    while len(sentence) < full:
+        options = matrix.successors((sentence[-2], sentence[-1]))
+        if not options:
+            return
+        total = 0.0
+        for _, p in options:
+            total += p
+        target = float(uniform[base + len(sentence) - 2]) * total
+        running, pick = 0.0, options[-1][0]
+        for w, p in options:
+            running += p
+            if running > target:
+                pick = w
+                break
+        sentence.append(pick)
+
+
+def _sentence_score(matrix: TriGramMatrix, sentence: Sequence[int]) -> float:
+    """1 + the tri-gram probabilities of all transitions, added left to right (M6)."""
+    score = 1.0
+    for a, b, w in zip(sentence, sentence[1:], sentence[2:]):
+        score = score + matrix.prob((a, b), w)
+    return score
+
+
+def _backup(node: Optional[SearchNode], score: float) -> None:
+    while node is not None:
+        node.visits += 1
+        node.score += score
+        node = node.parent
+
+
+def _ranked_leaf_paths(root: SearchNode, n: int) -> List[Tuple[float, List[int]]]:
+    """Root-to-leaf word lists with the leaf's accumulated score, best first, depth-first order among equals (M7)."""
+    found: List[Tuple[float, List[int]]] = []
+    stack: List[Tuple[SearchNode, List[int]]] = [(root, [])]
+    while stack:
+        node, words = stack.pop()
+        if not node.children:
+            if words:
+                found.append((node.score, words))
+            continue
+        for ch in reversed(node.children):  # popped in creation order
+            stack.append((ch, words + [ch.token]))
+    found.sort(key=lambda item: -item[0])  # stable
+    return found[:n]
 
 
 def run_mcts(matrix: TriGramMatrix, w0: int, w1: int, uniform: Sequence[float], iterations: int = 150, l: int = 4,
              n: int = 24, c1: float = 32.0, c2: float = 8.0, return_root: bool = False):
     """Alg. 1.  Returns [(score, [words])] best first (M7); with return_root also the search tree's root."""
-    sentence_length = l + 1  # M4
+    full = l + 2  # the root's two tokens plus l words (M4)
     assert len(uniform) >= iterations * l
-    root = Node(int(w0), int(w1), 1.0, matrix.successors((w0, w1)), None)
+    root = SearchNode((int(w0), int(w1)), 1.0, matrix.successors((w0, w1)), None)
     for it in range(iterations):
-        node = root
-        state = [node.word]
-        end = False
-        # Selection (M2)
-        while not node.untried_words and node.children and not end:
-            selected_child = node.select_child(c1, c2)
-            state.append(selected_child.word)
-            node = selected_child
-            if len(state) == sentence_length:
-                end = True
-        # Expansion (M3)
-        if node.untried_words and not end:
-            untried_words = node.untried_words
-            p_word = node.word[1]
-            for word, prior in untried_words:
-                tmp_untried_words = matrix.successors((p_word, word))
-                node.children.append(Node(p_word, word, prior, tmp_untried_words, node))
-            node.untried_words = []
-            node = node.children[-1]
-            state.append(node.word)
-        # Simulation (M5)
-        while len(state) < sentence_length:
-            last_word = state[-1]
-            next_words = matrix.successors(last_word)
-            if not next_words:
-                break
-            total = 0.0
-            for _, p in next_words:
-                total += p
-            target = float(uniform[it * l + (len(state) - 1)]) * total
-            cumulative, pick = 0.0, next_words[-1][0]
-            for w, p in next_words:
-                cumulative += p
-                if cumulative > target:
-                    pick = w
-                    break
-            state.append((last_word[1], pick))
-        # Backpropagation (M6)
-        score = 1.0
-        for i in range(1, len(state)):
-            score = score + matrix.prob(state[i - 1], state[i][1])
-        current_node = node
-        while current_node is not None:
-            current_node.visits += 1
-            current_node.score += score
-            current_node = current_node.parent
-    # Extract and sort (M7)
-    sentences: List[Tuple[float, List[int]]] = []
-
-    def walk(nd: Node, words: List[int]) -> None:
-        if not nd.children:
-            if words:
-                sentences.append((nd.score, list(words)))
-            return
-        for ch in nd.children:
-            words.append(ch.word[1])
-            walk(ch, words)
-            words.pop()
-
-    walk(root, [])
-    sentences.sort(key=lambda s: -s[0])  # stable: depth-first order among equal scores
-    sentences = sentences[:n]
-    return (sentences, root) if return_root else sentences
+        sentence = [int(w0), int(w1)]
+        node = _descend(root, sentence, full, c1, c2)
+        if node.pending and len(sentence) < full:
+            node = _expand(matrix, node)
+            sentence.append(node.token)
+        _rollout(matrix, sentence, full, uniform, it * l)
+        _backup(node, _sentence_score(matrix, sentence))
+    ranked = _ranked_leaf_paths(root, n)
+    return (ranked, root) if return_root else ranked

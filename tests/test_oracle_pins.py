@@ -606,6 +606,45 @@ def test_trigram_matrix_sums_and_window_brute_force():
     assert m.prob((99, 98), 1) == 0.0 and m.successors((99, 98)) == []
 
 
+def test_trigram_count_with_multiplicity_is_repeated_counting():
+    """count(doc, k) is Eq. (1)'s corpus with `doc` occurring k times: equal to k plain calls (same counts, same
+    successor order, same probabilities and the same elimination), a window-multiset brute force with weights, a
+    hand case, and times <= 0 adds nothing."""
+    import collections
+    g = np.random.default_rng(5)
+    docs = [(g.integers(0, 5, size=int(n)).tolist(), int(k)) for n, k in ((40, 3), (7, 1), (2, 9), (25, 0), (31, 12))]
+    a, b = dr.TriGramMatrix(), dr.TriGramMatrix()
+    for d, k in docs:
+        a.count(d, k)
+        for _ in range(k):
+            b.count(d)
+    assert a.c3 == b.c3 and a.c2 == b.c2
+    assert [list(r.items()) for r in a.c3.values()] == [list(r.items()) for r in b.c3.values()]  # insertion order too
+    windows = collections.Counter()
+    for d, k in docs:
+        for i in range(len(d) - 2):
+            windows[tuple(d[i:i + 3])] += k
+    starts = collections.Counter()
+    for w3, k in windows.items():
+        starts[w3[:2]] += k
+    for t in (1, 12, 20):
+        a.finalize(t)
+        b.finalize(t)
+        assert a.matrix == b.matrix and list(a.matrix.keys()) == list(b.matrix.keys())
+        for (x, y, z), k in windows.items():
+            assert a.prob((x, y), z) == (k / starts[(x, y)] if k >= t and k > 0 else 0.0)
+    # by hand: "1 2 3" five times and "1 2 4" once give P(3 | 1 2) = 5/6, P(4 | 1 2) = 1/6; t = 2 drops the latter
+    m = dr.TriGramMatrix()
+    m.count([1, 2, 3], 5)
+    m.count([1, 2, 4])
+    m.count([1, 2, 4], 0)
+    m.count([1, 2, 4], -3)
+    m.finalize(1)
+    assert m.successors((1, 2)) == [(3, 5 / 6), (4, 1 / 6)]
+    m.finalize(2)
+    assert m.successors((1, 2)) == [(3, 5 / 6)]
+
+
 def test_puct_hand_values_and_shape():
     _, pu = _drafter_golden()
     assert len(pu) == 4
@@ -689,7 +728,7 @@ def test_mcts_first_iteration_by_hand_and_inverse_cdf():
     # simulates one word after the pair (2, 4); l = 2, so the draw uses uniform[0 * 2 + 1]
     for u, pick, p_pick in ((0.0, 5, 0.5), (0.49, 5, 0.5), (0.5, 6, 0.3), (0.79, 6, 0.3), (0.8, 7, 0.2), (0.999, 7, 0.2)):
         _, root = dr.run_mcts(m, 1, 2, [0.123, u], iterations=1, l=2, return_root=True)
-        assert [c.word for c in root.children] == [(2, 3), (2, 4)]
+        assert [c.context for c in root.children] == [(2, 3), (2, 4)]
         assert [c.visits for c in root.children] == [0, 1]
         assert abs(root.score - (1.0 + 0.75 + p_pick)) < 1e-15, (u, pick)
     # unnormalised successors (after an update): weights are relative to their sum 1.5
@@ -737,8 +776,8 @@ def test_mcts_invariants_on_random_matrices():
                 assert nd.score >= sum(c.score for c in nd.children) - 1e-9
                 if not own:
                     assert abs(nd.score - sum(c.score for c in nd.children)) < 1e-9 * max(1.0, nd.score)
-                assert not nd.untried_words
-                assert [c.word[1] for c in nd.children] == [w for w, _ in m.successors(nd.word)]
+                assert not nd.pending
+                assert [c.token for c in nd.children] == [w for w, _ in m.successors(nd.context)]
             else:
                 leaves += 1
         assert len(sent) == min(n, leaves if root.children else 0)
