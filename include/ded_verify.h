@@ -40,7 +40,8 @@ enum {
   DED_ECAP = -4,   /* prefix_len + n_nodes exceeds kv_capacity, or a size exceeds its maximum */
   DED_ESTATE = -5, /* call out of order (e.g. ded_accept without a pending step) */
   DED_EHIP = -6,   /* a HIP runtime call failed */
-  DED_ENOMEM = -7  /* workspace too small / host allocation failed */
+  DED_ENOMEM = -7, /* workspace too small / host allocation failed */
+  DED_ENONFINITE = -8 /* the logits of a tree node hold a NaN or an infinity (see ded_accept) */
 };
 
 enum { DED_F32 = 0, DED_BF16 = 1 };
@@ -191,7 +192,10 @@ void ded_verify_free(ded_ctx *ctx);
  *   logits_out  device fp32 [batch][max_nodes][vocab] or NULL; when given, the rows of the real
  *               nodes are written there (rows of absent nodes are left untouched)
  * Effects: K/V of node i of sequence b are written to cache slot prefix_len[b] + i (scratch until
- * accepted); the per-node argmax and top-1/top-2 margin are kept in the workspace.
+ * accepted); the per-node argmax and top-1/top-2 margin are kept in the workspace.  With DED_BF16 the
+ * [rows][vocab] logits themselves reach memory only when logits_out is given or the context has been
+ * used with ded_sample before: otherwise the LM-head GEMM hands the argmax its per-tile candidates
+ * directly (same tokens and margins, bit for bit).
  * Errors: DED_EINVAL, DED_ETREE, DED_ETOKEN, DED_ECAP, DED_EHIP.  On error nothing was launched. */
 int ded_verify_step(ded_ctx *ctx, int32_t batch, const int32_t *prefix_len, const int32_t *n_nodes,
                     const int32_t *parent, const int32_t *token, float *logits_out);
@@ -206,7 +210,9 @@ int ded_verify_step(ded_ctx *ctx, int32_t batch, const int32_t *prefix_len, cons
  *   temperature > 0, 0 < top_p <= 1
  *   uniform  host [batch][max_nodes], one number in [0, 1) per node, drawn by the caller
  * Synchronises the stream.  ded_get_argmax afterwards returns the sampled tokens (margins unchanged).
- * Errors: DED_EINVAL (range of an argument, null), DED_ESTATE (no pending step), DED_EHIP. */
+ * The first sampled step of a DED_BF16 context runs the LM head once more to obtain the logits that the
+ * step did not keep; later steps of that context keep them.
+ * Errors: DED_EINVAL (range of an argument, null), DED_ESTATE (no pending step), DED_ENONFINITE, DED_EHIP. */
 int ded_sample(ded_ctx *ctx, float temperature, float top_p, const float *uniform);
 
 /* Approval walk + cache compaction for the pending step (Sec. 2.4: a draft token is approved when
@@ -220,12 +226,19 @@ int ded_sample(ded_ctx *ctx, float temperature, float top_p, const float *unifor
  *   compaction_idx  [batch][max_nodes+1]  node indices of the kept path, root first
  *   new_prefix_len  [batch]               prefix_len + path length
  * The K/V of path node j move to slot prefix_len + j; slots beyond new_prefix_len are dead.
- * Synchronises the stream.  Errors: DED_EINVAL, DED_ESTATE, DED_ETREE (mode 1, not a chain), DED_EHIP. */
+ * Non-finite values: if the logits of any real node of a sequence hold a NaN or an infinity (weights that
+ * are not finite, or activations beyond the half-precision range of the DED_BF16 matrix-core operands,
+ * |x * gain| > 65504), there is no meaningful model token: the call returns DED_ENONFINITE, writes no
+ * output, keeps nothing of ANY sequence of the batch (every cache is as it was before the step; the
+ * slots the step appended are zeroed) and the step is consumed.
+ * Synchronises the stream.  Errors: DED_EINVAL, DED_ESTATE, DED_ETREE (mode 1, not a chain),
+ * DED_ENONFINITE, DED_EHIP. */
 int ded_accept(ded_ctx *ctx, int32_t mode, int32_t *accepted_tokens, int32_t *n_accepted,
                int32_t *compaction_idx, int32_t *new_prefix_len);
 
 /* Per-node model tokens of the last step: argmax host [batch][max_nodes] (lowest id on exact ties),
- * margin host [batch][max_nodes] or NULL (top-1 minus top-2 logit).  Synchronises the stream. */
+ * margin host [batch][max_nodes] or NULL (top-1 minus top-2 logit).  Synchronises the stream.
+ * DED_ENONFINITE (nothing written) if the logits of a real node hold a NaN or an infinity. */
 int ded_get_argmax(ded_ctx *ctx, int32_t *argmax, float *margin);
 
 /* Plain <-> library layout for `n` cache slots starting at `first_slot` of sequence `seq`, layer

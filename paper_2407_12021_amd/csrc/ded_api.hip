@@ -25,12 +25,12 @@ inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 enum KClass {
   KC_META = 0, KC_ROPE_TABLE, KC_EMBED, KC_RMSNORM, KC_GEMM_QKV, KC_QKV_EPILOGUE, KC_TREE_ATTN, KC_ATTN_MERGE,
   KC_GEMM_O, KC_GEMM_GATE_UP, KC_SILU_MUL, KC_GEMM_DOWN, KC_GEMM_LM_HEAD, KC_ARGMAX, KC_EXPORT, KC_WALK,
-  KC_COMPACT, KC_LAYOUT, KC_SAMPLE, KC_COUNT
+  KC_COMPACT, KC_LAYOUT, KC_SAMPLE, KC_TOP2_REDUCE, KC_COUNT
 };
 const char* const kClassNames[KC_COUNT] = {
     "meta_upload", "rope_table", "embed", "add_rmsnorm", "gemm_qkv", "qkv_rope_epilogue", "tree_attention",
     "attention_merge", "gemm_o", "gemm_gate_up", "silu_mul", "gemm_down", "gemm_lm_head", "argmax",
-    "export_logits", "accept_walk", "kv_compact", "layout_convert", "sample_top_p"};
+    "export_logits", "accept_walk", "kv_compact", "layout_convert", "sample_top_p", "top2_reduce"};
 
 struct Carve {  // bump allocator over the workspace (base may be null when only sizing)
   char* base;
@@ -108,6 +108,7 @@ struct ded_ctx {
   float* attn_part_o = nullptr;
   float2* attn_part_ml = nullptr;
   int64_t attn_part_rows = 0;
+  void* top2_part = nullptr;  // [rows_pad][ceil(V / 64)] x 16 B: per-group candidates of the fused LM-head argmax
   // step meta (device + pinned host mirror, one contiguous block)
   char* d_meta = nullptr;
   char* h_meta = nullptr;
@@ -118,13 +119,18 @@ struct ded_ctx {
   // results
   int32_t* d_amax = nullptr;
   float* d_margin = nullptr;
+  int32_t* d_rowflag = nullptr;  // [rows] != 0: the row's logits hold a NaN or an infinity
+  int32_t* d_seqflag = nullptr;  // [max_batch] the same per sequence (real nodes only), written by the walk
   float* d_uniform = nullptr;  // [rows] uniform numbers of ded_sample
   int32_t *d_nacc = nullptr, *d_path = nullptr, *d_acctok = nullptr;
-  char* h_res = nullptr;  // pinned: amax | margin | nacc | path | acctok
+  char* h_res = nullptr;  // pinned: amax | margin | row flags, or nacc | seqflag | path | acctok
   size_t res_bytes = 0;
   // state of the pending step
   bool pending = false;
   bool have_argmax = false;
+  bool have_logits = false;    // the workspace holds the fp32 logits of the last step
+  bool poisoned = false;       // the last step's tree slots may hold NaN / infinite K/V: cleared before they can be read
+  bool sampling_seen = false;  // ded_sample has been used on this context: steps keep their logits from then on
   int batch = 0, n_step = 0;
   int max_p = 0;
   std::vector<int32_t> s_p, s_n, s_parent;
@@ -280,7 +286,9 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
     int64_t arows = std::max<int64_t>(kAttnPartRows, (int64_t)z.max_rows * c.n_heads);
     float* apo = w.take<float>(arows * c.head_dim);
     float2* apm = w.take<float2>(arows);
+    char* t2 = w.take<char>((size_t)z.max_rows_pad * ((V + 63) / 64) * 16);
     if (ctx) {
+      ctx->top2_part = t2;
       ctx->y_p = y;
       ctx->o_p = o;
       ctx->h_p = h;
@@ -312,9 +320,11 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
   int32_t* amax = w.take<int32_t>(z.max_rows_pad);
   float* margin = w.take<float>(z.max_rows_pad);
   float* uniform = w.take<float>(z.max_rows_pad);
-  // one block, so that a single copy brings a step's verdict to the host: nacc | path | acctok
-  int32_t* nacc = w.take<int32_t>((int64_t)c.max_batch * (1 + 2 * stride));
-  int32_t* path = nacc + c.max_batch;
+  int32_t* rowflag = w.take<int32_t>(z.max_rows_pad);
+  // one block, so that a single copy brings a step's verdict to the host: nacc | seqflag | path | acctok
+  int32_t* nacc = w.take<int32_t>((int64_t)c.max_batch * (2 + 2 * stride));
+  int32_t* seqflag = nacc + c.max_batch;
+  int32_t* path = seqflag + c.max_batch;
   int32_t* acct = path + (int64_t)c.max_batch * stride;
   if (ctx) {
     ctx->d_meta = dmeta;
@@ -329,6 +339,8 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
     ctx->d_amax = amax;
     ctx->d_margin = margin;
     ctx->d_uniform = uniform;
+    ctx->d_rowflag = rowflag;
+    ctx->d_seqflag = seqflag;
     ctx->d_nacc = nacc;
     ctx->d_path = path;
     ctx->d_acctok = acct;
@@ -504,7 +516,51 @@ int forward_f32(ded_ctx* c) {
   return launch_status();
 }
 
-int forward_bf16(ded_ctx* c) {
+// After a step whose logits were not finite the K/V it appended (slots prefix_len .. prefix_len + n_nodes of every
+// sequence, every layer) may be NaN or infinite.  Dead slots are still fetched by whole-tile loads (and multiplied
+// by a zero weight), so they are zeroed before any later step can fetch them.
+int clear_step_slots(ded_ctx* c) {
+  for (int l = 0; l < c->md.n_layers; ++l)
+    for (int b = 0; b < c->batch; ++b) {
+      if (c->bf16) bf16_kv_clear((bf16_t*)c->kc[l], (bf16_t*)c->vc[l], b, c->s_p[b], c->s_n[b], c->md, c->stream);
+      else f32_kv_clear((float*)c->kc[l], (float*)c->vc[l], b, c->s_p[b], c->s_n[b], c->md, c->stream);
+    }
+  c->poisoned = false;
+  return launch_status();
+}
+
+// LM head of the 16-bit path on the final residual stream (c->y_p / c->ssq as the last layer left them).  With
+// want_logits the fp32 logits are written to the workspace; without, only the per-group top-2 candidates that the
+// per-node argmax needs (the logits never reach memory).
+bool lm_head_bf16(ded_ctx* c, bool want_logits) {
+  const ModelDims& md = c->md;
+  const int rows = c->batch * c->n_step, rows_pad = round_up(rows, 64), d = md.d;
+  GemmEpilogue e = {};
+  e.rows = rows;
+  e.rb_total = rows_pad / 16;
+  e.eps = md.eps;
+  e.ssq_in = c->ssq;
+  e.ssq_groups = d / 64;
+  e.inv_k = 1.0f / (float)d;
+  if (want_logits) {
+    e.kind = EPI_LOGITS;
+    e.out = c->logits;
+    e.out_stride = md.V;
+  } else {
+    e.kind = EPI_TOP2;
+    e.top2_part = c->top2_part;
+    e.top2_groups = (md.V + 63) / 64;
+  }
+  const int64_t slice = (int64_t)rows_pad * round_up(md.V, 64);
+  int cap = (int)std::min<int64_t>(8, c->part_elems / slice);
+  GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, 2, std::max(cap, 1));
+  if (bf16_gemm_tiles(rows_pad, md.V, plan) > kGemmCounters) plan.splits = 1;
+  ProfScope p(c, KC_GEMM_LM_HEAD);
+  return bf16_gemm(c->part, slice, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 2, plan, c->counters, e,
+                   c->stream);
+}
+
+int forward_bf16(ded_ctx* c, bool want_logits) {
   const ModelDims& md = c->md;
   StepMeta m = c->meta();
   hipStream_t s = c->stream;
@@ -583,14 +639,7 @@ int forward_bf16(ded_ctx* c) {
       gemm(KC_GEMM_DOWN, c->h_p, c->wdown[l], d, F, 1, e);
     }
   }
-  {
-    GemmEpilogue e = base;
-    e.kind = EPI_LOGITS;
-    normed_input(e);
-    e.out = c->logits;
-    e.out_stride = md.V;
-    gemm(KC_GEMM_LM_HEAD, c->y_p, c->lm_head, md.V, d, 2, e);
-  }
+  ok = lm_head_bf16(c, want_logits) && ok;
   if (!ok) return DED_EINVAL;
   return launch_status();
 }
@@ -610,6 +659,7 @@ const char* ded_strerror(int code) {
     case DED_ESTATE: return "call out of order";
     case DED_EHIP: return "HIP runtime failure";
     case DED_ENOMEM: return "workspace too small or host allocation failed";
+    case DED_ENONFINITE: return "NaN or infinity in the logits of a tree node (weights or activations outside the half-precision operand range?)";
     default: return "unknown error";
   }
 }
@@ -679,7 +729,7 @@ int ded_verify_init(const ded_config* cfg, const ded_weights* w, const ded_kv* k
     return code;
   };
   int stride = cfg->max_nodes + 1;
-  c->res_bytes = align_up((size_t)z.max_rows_pad * 8 + (size_t)cfg->max_batch * 4 * (1 + 2 * stride), 256);
+  c->res_bytes = align_up((size_t)z.max_rows_pad * 12 + (size_t)cfg->max_batch * 4 * (2 + 2 * stride), 256);
   if (hipHostMalloc(reinterpret_cast<void**>(&c->h_meta), c->meta_bytes, hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc(reinterpret_cast<void**>(&c->h_res), c->res_bytes, hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
@@ -764,14 +814,25 @@ int ded_verify_step(ded_ctx* c, int32_t batch, const int32_t* prefix_len, const 
   if (!c) return DED_EINVAL;
   int rc = validate_step(c->cfg, batch, prefix_len, n_nodes, parent, token, true);
   if (rc != DED_OK) return rc;
+  if (c->poisoned && (rc = clear_step_slots(c)) != DED_OK) return rc;
   rc = ingest_and_upload(c, batch, prefix_len, n_nodes, parent, token);
   if (rc != DED_OK) return rc;
   c->pending = false;
   c->have_argmax = false;
-  rc = c->bf16 ? forward_bf16(c) : forward_f32(c);
+  // the fp32 logits are materialised only for a caller that asks for them or samples from them
+  const bool want_logits = !c->bf16 || logits_out != nullptr || c->sampling_seen;
+  c->have_logits = false;
+  rc = c->bf16 ? forward_bf16(c, want_logits) : forward_f32(c);
   if (rc != DED_OK) return rc;
   StepMeta m = c->meta();
-  { ProfScope p(c, KC_ARGMAX); launch_argmax(c->logits, c->md.V, m.rows, c->md.V, c->d_amax, c->d_margin, c->stream); }
+  if (want_logits) {
+    ProfScope p(c, KC_ARGMAX);
+    launch_argmax(c->logits, c->md.V, m.rows, c->md.V, c->d_amax, c->d_margin, c->d_rowflag, c->stream);
+  } else {
+    ProfScope p(c, KC_TOP2_REDUCE);
+    launch_top2_reduce(c->top2_part, (c->md.V + 63) / 64, m.rows, c->d_amax, c->d_margin, c->d_rowflag, c->stream);
+  }
+  c->have_logits = want_logits;
   if (logits_out) {
     ProfScope p(c, KC_EXPORT);
     launch_export_logits(logits_out, c->logits, c->md.V, m, c->cfg.max_nodes, c->md.V, c->stream);
@@ -796,7 +857,8 @@ int ded_accept(ded_ctx* c, int32_t mode, int32_t* accepted_tokens, int32_t* n_ac
   }
   StepMeta m = c->meta();
   hipStream_t s = c->stream;
-  { ProfScope p(c, KC_WALK); launch_accept_walk(m, c->d_amax, mode, c->d_nacc, c->d_path, c->d_acctok, stride, s); }
+  { ProfScope p(c, KC_WALK);
+    launch_accept_walk(m, c->d_amax, c->d_rowflag, mode, c->d_nacc, c->d_seqflag, c->d_path, c->d_acctok, stride, s); }
   if (c->md.n_layers > 0 && mode == 0) {
     ProfScope p(c, KC_COMPACT);
     if (c->bf16)
@@ -807,13 +869,20 @@ int ded_accept(ded_ctx* c, int32_t mode, int32_t* accepted_tokens, int32_t* n_ac
   if (launch_status() != DED_OK) return DED_EHIP;
   int32_t* h_n = reinterpret_cast<int32_t*>(c->h_res);
   const int MB = c->cfg.max_batch;
-  int32_t* h_path = h_n + MB;
+  int32_t* h_flag = h_n + MB;
+  int32_t* h_path = h_flag + MB;
   int32_t* h_tok = h_path + (size_t)MB * stride;
-  // nacc | path | acctok are one device block with the same layout: path and acctok of the live sequences end
-  // before (MB + (MB + B) * stride) words
-  HIP_TRY(hipMemcpyAsync(h_n, c->d_nacc, sizeof(int32_t) * ((size_t)MB + (size_t)(MB + B) * stride),
+  // nacc | seqflag | path | acctok are one device block with the same layout: path and acctok of the live
+  // sequences end before (2 MB + (MB + B) * stride) words
+  HIP_TRY(hipMemcpyAsync(h_n, c->d_nacc, sizeof(int32_t) * (2 * (size_t)MB + (size_t)(MB + B) * stride),
                          hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  c->pending = false;
+  for (int b = 0; b < B; ++b)
+    if (h_flag[b]) {  // the walk kept nothing: every sequence's cache is as it was before the step
+      int rc = clear_step_slots(c);
+      return rc != DED_OK ? rc : DED_ENONFINITE;
+    }
   for (int b = 0; b < B; ++b) {
     int len = h_n[b];
     if (len < 1 || len > c->s_n[b]) return DED_EHIP;
@@ -822,7 +891,6 @@ int ded_accept(ded_ctx* c, int32_t mode, int32_t* accepted_tokens, int32_t* n_ac
     memcpy(accepted_tokens + (size_t)b * stride, h_tok + (size_t)b * stride, sizeof(int32_t) * len);
     memcpy(compaction_idx + (size_t)b * stride, h_path + (size_t)b * stride, sizeof(int32_t) * len);
   }
-  c->pending = false;
   return DED_OK;
 }
 
@@ -839,10 +907,25 @@ int ded_sample(ded_ctx* c, float temperature, float top_p, const float* uniform)
       h_u[b * c->n_step + i] = u;
     }
   HIP_TRY(hipMemcpyAsync(c->d_uniform, h_u, sizeof(float) * rows, hipMemcpyHostToDevice, c->stream));
+  // A step keeps its logits only if the caller asked for them or the context has sampled before; the first
+  // sampled step of a context recomputes them from the final residual stream, which is still in place.
+  c->sampling_seen = true;
+  if (!c->have_logits) {
+    if (!lm_head_bf16(c, true)) return DED_EINVAL;
+    c->have_logits = true;
+  }
   { ProfScope p(c, KC_SAMPLE);
     launch_sample_top_p(c->logits, c->md.V, rows, c->md.V, temperature, top_p, c->d_uniform, c->d_amax, c->stream); }
   if (launch_status() != DED_OK) return DED_EHIP;
+  int32_t* h_f = reinterpret_cast<int32_t*>(c->h_res) + c->max_rows_pad;
+  HIP_TRY(hipMemcpyAsync(h_f, c->d_rowflag, sizeof(int32_t) * rows, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));  // h_res is free again
+  for (int b = 0; b < c->batch; ++b)
+    for (int i = 0; i < c->s_n[b]; ++i)
+      if (h_f[b * c->n_step + i]) {
+        c->poisoned = true;
+        return DED_ENONFINITE;
+      }
   return DED_OK;
 }
 
@@ -854,7 +937,15 @@ int ded_get_argmax(ded_ctx* c, int32_t* argmax, float* margin) {
   float* h_m = reinterpret_cast<float*>(c->h_res) + c->max_rows_pad;
   HIP_TRY(hipMemcpyAsync(h_a, c->d_amax, sizeof(int32_t) * rows, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(hipMemcpyAsync(h_m, c->d_margin, sizeof(float) * rows, hipMemcpyDeviceToHost, c->stream));
+  int32_t* h_f = reinterpret_cast<int32_t*>(c->h_res) + 2 * (size_t)c->max_rows_pad;
+  HIP_TRY(hipMemcpyAsync(h_f, c->d_rowflag, sizeof(int32_t) * rows, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
+  for (int b = 0; b < c->batch; ++b)
+    for (int i = 0; i < c->s_n[b]; ++i)
+      if (h_f[b * c->n_step + i]) {
+        c->poisoned = true;
+        return DED_ENONFINITE;
+      }
   for (int b = 0; b < c->batch; ++b)
     for (int i = 0; i < c->s_n[b]; ++i) {
       argmax[(size_t)b * mn + i] = h_a[b * c->n_step + i];
@@ -907,6 +998,7 @@ static int tree_attention_common(ded_ctx* c, int32_t layer, int32_t batch, const
   if (layer < 0 || layer >= c->md.n_layers) return DED_EINVAL;
   int rc = validate_step(c->cfg, batch, prefix_len, n_nodes, parent, nullptr, false);
   if (rc != DED_OK) return rc;
+  if (c->poisoned && (rc = clear_step_slots(c)) != DED_OK) return rc;
   const ModelDims& md = c->md;
   AttnScratch ws = {c->d_meta, c->q_p, c->o_p, c->attn_part_o, c->attn_part_ml, c->attn_part_rows};
   int ns = 1;

@@ -28,9 +28,13 @@ struct ModelDims {
 // ---- shared (both dtypes) --------------------------------------------------------------
 // cos/sin of pos[r] * base^(-2i/hd), i < hd/2, angles formed in fp64.  tab: [R][hd/2] float2.
 void launch_rope_table(float2* tab, const int32_t* pos, int rows, int hd, float base, hipStream_t s);
-// Per-row argmax (lowest index on exact ties) and top-1 minus top-2 over V fp32 logits.
+// Per-row argmax (lowest index on exact ties) and top-1 minus top-2 over V fp32 logits; flag[r] != 0 when the
+// row holds a NaN or an infinity.
 void launch_argmax(const float* logits, int64_t row_stride, int rows, int V, int32_t* amax,
-                   float* margin, hipStream_t s);
+                   float* margin, int32_t* flag, hipStream_t s);
+// The same from the candidates the LM-head GEMM leaves with EPI_TOP2: part [rows][groups] x 16 bytes.
+void launch_top2_reduce(const void* part, int groups, int rows, int32_t* amax, float* margin, int32_t* flag,
+                        hipStream_t s);
 // Per-row temperature / top-p sample (inverse CDF of uniform[r] over the nucleus in id order) -> token_out[r].
 void launch_sample_top_p(const float* logits, int64_t row_stride, int rows, int V, float temperature, float top_p,
                          const float* uniform, int32_t* token_out, hipStream_t s);
@@ -38,9 +42,9 @@ void launch_sample_top_p(const float* logits, int64_t row_stride, int rows, int 
 void launch_export_logits(float* dst, const float* src, int64_t src_stride, const StepMeta& m,
                           int max_nodes, int V, hipStream_t s);
 // Approval walk (one wavefront per sequence).  mode 0 greedy, mode 1 keep the whole chain.
-// out_n [B], out_path / out_tok [B][stride].
-void launch_accept_walk(const StepMeta& m, const int32_t* amax, int mode, int32_t* out_n,
-                        int32_t* out_path, int32_t* out_tok, int stride, hipStream_t s);
+// out_n [B], out_path / out_tok [B][stride].  If a real row of any sequence is flagged, every sequence gets out_n = 0, out_flag = 1.
+void launch_accept_walk(const StepMeta& m, const int32_t* amax, const int32_t* row_flag, int mode, int32_t* out_n,
+                        int32_t* out_flag, int32_t* out_path, int32_t* out_tok, int stride, hipStream_t s);
 
 // ---- fp32 path (plain row-major everywhere; cache [B][Hkv][cap][hd]) ---------------------
 void f32_embed(float* x, const float* emb, const StepMeta& m, int d, hipStream_t s);
@@ -57,6 +61,7 @@ void f32_kv_compact(float* const* kc, float* const* vc, const int32_t* path, con
 // plain [Hkv][n][hd] <-> cache
 void f32_kv_copy(float* cache, float* plain, bool to_cache, int seq, int first, int n,
                  const ModelDims& md, hipStream_t s);
+void f32_kv_clear(float* kc, float* vc, int seq, int first, int n, const ModelDims& md, hipStream_t s);
 void f32_scatter_tree_kv(float* kc, float* vc, const float* k_tree, const float* v_tree,
                          const StepMeta& m, const ModelDims& md, int max_nodes, hipStream_t s);
 // q [B][max_nodes][H][hd] -> qkv-style rows [R][H*hd]; and back for the output
@@ -84,7 +89,7 @@ void bf16_embed(float* x, bf16_t* y_packed, float* ssq, const bf16_t* emb, const
 
 // What a GEMM does with its result tile (fused epilogue).  RMSNorm is deferred: producers write
 // x * gain and sum(x^2) per 64-feature group, consumers multiply their output rows by 1/rms.
-enum { EPI_LOGITS = 0, EPI_QKV = 1, EPI_SILU = 2, EPI_RESIDUAL = 3 };
+enum { EPI_LOGITS = 0, EPI_QKV = 1, EPI_SILU = 2, EPI_RESIDUAL = 3, EPI_TOP2 = 4 };
 struct GemmEpilogue {
   int kind;
   // row scale of the GEMM input (null: 1): scale[r] = rsqrt(sum_g ssq_in[r][g] * inv_k + eps)
@@ -96,6 +101,10 @@ struct GemmEpilogue {
   // EPI_LOGITS: out[r][n] = scale * Y
   float* out;
   int64_t out_stride;
+  // EPI_TOP2: instead of the logits, per (row, 64-feature group) the best value, its feature index, the second
+  // best value and a non-finite flag: top2_part[r * top2_groups + group] (16 bytes each)
+  void* top2_part;
+  int top2_groups;
   // EPI_QKV: rotary embedding at the row's position, queries -> PackQ (hi/lo), keys / values -> cache
   bf16_t *q_packed, *k_cache, *v_cache;
   const float2* rope_tab;
@@ -136,6 +145,7 @@ void bf16_kv_compact(bf16_t* const* kc, bf16_t* const* vc, const int32_t* path, 
                      const StepMeta& m, const ModelDims& md, int stride, hipStream_t s);
 void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_plain, bool to_cache,
                   int seq, int first, int n, const ModelDims& md, hipStream_t s);
+void bf16_kv_clear(bf16_t* kcache, bf16_t* vcache, int seq, int first, int n, const ModelDims& md, hipStream_t s);
 void bf16_scatter_tree_kv(bf16_t* kc, bf16_t* vc, const bf16_t* k_tree, const bf16_t* v_tree,
                           const StepMeta& m, const ModelDims& md, int max_nodes, hipStream_t s);
 void bf16_pack_q(bf16_t* q_packed, const bf16_t* q_plain, const StepMeta& m, const ModelDims& md,

@@ -258,6 +258,49 @@ __device__ inline void run_epilogue(const GemmEpilogue& e, int ng, int N, int rb
         *reinterpret_cast<float4*>(e.out + r * e.out_stride + n) = make_float4(v[0], v[1], v[2], v[3]);
       }
     }
+  } else if (EPI == EPI_TOP2) {
+    // what the approval walk needs of a logits row, without the row: the best value of this 64-feature group, its
+    // feature index (lowest on ties), the second best value, and whether any value is NaN or infinite
+    uint4* dst = reinterpret_cast<uint4*>(e.top2_part);
+#pragma unroll
+    for (int rb = 0; rb < RBN; ++rb) {
+      const int64_t r = (int64_t)(rbase + rb) * 16 + row_in;
+      float v1 = -INFINITY, v2 = -INFINITY;
+      int i1 = 0x7fffffff, bad = 0;
+#pragma unroll
+      for (int t = 0; t < TN; ++t) {
+        const int n = (ng * TN + t) * 16 + quad * 4;
+        if (n >= N) continue;
+        const f32x4_t v = acc[t][rb] * scale[rb];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // ascending feature index: a later equal value never replaces the first
+          const float x = v[i];
+          bad |= !(fabsf(x) <= 3.402823466e38f);
+          if (x > v1) {
+            v2 = v1;
+            v1 = x;
+            i1 = n + i;
+          } else if (x > v2) {
+            v2 = x;
+          }
+        }
+      }
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {  // the four lanes that share the row
+        const float ov1 = __shfl_xor(v1, off), ov2 = __shfl_xor(v2, off);
+        const int oi1 = __shfl_xor(i1, off);
+        bad |= __shfl_xor(bad, off);
+        if (ov1 > v1 || (ov1 == v1 && oi1 < i1)) {
+          v2 = fmaxf(v1, ov2);
+          v1 = ov1;
+          i1 = oi1;
+        } else {
+          v2 = fmaxf(v2, ov1);
+        }
+      }
+      if (quad == 0)
+        dst[r * e.top2_groups + ng] = make_uint4(__float_as_uint(v1), (uint32_t)i1, __float_as_uint(v2), (uint32_t)bad);
+    }
   } else if (EPI == EPI_RESIDUAL) {
     // x += Y;  next GEMM input = (x * gain) as hi/lo f16 (its 1/rms is applied by the consumer);  sum(x^2) per group
 #pragma unroll
@@ -1038,6 +1081,9 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
   switch (epi.kind) {
     case EPI_LOGITS:
       if (planes == 2) DED_GO(2, EPI_LOGITS);
+      return false;
+    case EPI_TOP2:
+      if (planes == 2) DED_GO(2, EPI_TOP2);
       return false;
     case EPI_QKV:
       if (planes == 2) DED_GO(2, EPI_QKV);

@@ -212,6 +212,20 @@ void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_pla
                      to_cache ? 1 : 0, seq, first, n, md.Hkv, md.cap);
 }
 
+// zero the slots [first, first + n) of one sequence (keys and values) in the fragment layouts
+__global__ void bf16_kv_clear_kernel(bf16_t* __restrict__ kcache, bf16_t* __restrict__ vcache, int seq, int first,
+                                     int Hkv, int cap) {
+  const int hd = 128;
+  int j = blockIdx.x, g = blockIdx.y, i = threadIdx.x;
+  int64_t cbase = ((int64_t)seq * Hkv + g) * cap * hd;
+  kcache[cbase + packk_index(first + j, i)] = 0;
+  vcache[cbase + packvt_index(first + j, i)] = 0;
+}
+void bf16_kv_clear(bf16_t* kcache, bf16_t* vcache, int seq, int first, int n, const ModelDims& md, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(bf16_kv_clear_kernel, dim3(n, md.Hkv), dim3(128), 0, s, kcache, vcache, seq, first, md.Hkv, md.cap);
+}
+
 __global__ void bf16_scatter_tree_kv_kernel(bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
                                             const bf16_t* __restrict__ kt, const bf16_t* __restrict__ vt,
                                             const int32_t* __restrict__ seq_p, const int32_t* __restrict__ seq_n,

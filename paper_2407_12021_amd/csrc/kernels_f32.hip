@@ -277,6 +277,21 @@ void f32_kv_copy(float* cache, float* plain, bool to_cache, int seq, int first, 
                      first, n, md.Hkv, md.hd, md.cap);
 }
 
+// zero the slots [first, first + n) of one sequence (keys and values)
+__global__ void f32_kv_clear_kernel(float* __restrict__ kc, float* __restrict__ vc, int seq, int first, int Hkv,
+                                    int hd, int cap) {
+  int j = blockIdx.x, g = blockIdx.y;
+  int64_t at = (((int64_t)seq * Hkv + g) * cap + first + j) * hd;
+  for (int i = threadIdx.x; i < hd; i += blockDim.x) {
+    kc[at + i] = 0.f;
+    vc[at + i] = 0.f;
+  }
+}
+void f32_kv_clear(float* kc, float* vc, int seq, int first, int n, const ModelDims& md, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(f32_kv_clear_kernel, dim3(n, md.Hkv), dim3(64), 0, s, kc, vc, seq, first, md.Hkv, md.hd, md.cap);
+}
+
 // k_tree / v_tree: [B][Hkv][max_nodes][hd] -> cache slot P + node
 __global__ void f32_scatter_tree_kv_kernel(float* __restrict__ kc, float* __restrict__ vc,
                                            const float* __restrict__ kt, const float* __restrict__ vt,

@@ -56,44 +56,88 @@ __device__ inline void top2_merge(Top2& a, const Top2& b) {
   }
 }
 
-__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int64_t row_stride,
-                                                     int V, int32_t* __restrict__ amax,
-                                                     float* __restrict__ margin) {
-  const float* row = logits + (int64_t)blockIdx.x * row_stride;
-  Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
-  int nv4 = ((reinterpret_cast<uintptr_t>(row) & 15) == 0) ? (V / 4) : 0;
-  const float4* row4 = reinterpret_cast<const float4*>(row);
-  for (int i = threadIdx.x; i < nv4; i += 256) {
-    float4 v = row4[i];
-    top2_push(t, v.x, 4 * i);
-    top2_push(t, v.y, 4 * i + 1);
-    top2_push(t, v.z, 4 * i + 2);
-    top2_push(t, v.w, 4 * i + 3);
-  }
-  for (int i = nv4 * 4 + threadIdx.x; i < V; i += 256) top2_push(t, row[i], i);
+// NaN and +-inf: a row that holds one has no meaningful argmax; it is reported through the row's flag
+__device__ inline int nonfinite(float v) { return !(fabsf(v) <= 3.402823466e38f); }
+
+// combine the 256 threads' candidates of one row and write the row's verdict
+__device__ inline void top2_block_finish(Top2 t, int bad, int32_t* amax, float* margin, int32_t* flag) {
   for (int off = 32; off >= 1; off >>= 1) {
     Top2 o;
     o.v1 = __shfl_xor(t.v1, off);
     o.i1 = __shfl_xor(t.i1, off);
     o.v2 = __shfl_xor(t.v2, off);
     top2_merge(t, o);
+    bad |= __shfl_xor(bad, off);
   }
   __shared__ Top2 sh[4];
+  __shared__ int sh_bad[4];
   int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) sh[wave] = t;
+  if ((threadIdx.x & 63) == 0) {
+    sh[wave] = t;
+    sh_bad[wave] = bad;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     Top2 r = sh[0];
     for (int w = 1; w < 4; ++w) top2_merge(r, sh[w]);
     amax[blockIdx.x] = r.i1;
     margin[blockIdx.x] = r.v1 - r.v2;
+    flag[blockIdx.x] = sh_bad[0] | sh_bad[1] | sh_bad[2] | sh_bad[3];
   }
 }
 
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int64_t row_stride,
+                                                     int V, int32_t* __restrict__ amax,
+                                                     float* __restrict__ margin, int32_t* __restrict__ flag) {
+  const float* row = logits + (int64_t)blockIdx.x * row_stride;
+  Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
+  int bad = 0;
+  int nv4 = ((reinterpret_cast<uintptr_t>(row) & 15) == 0) ? (V / 4) : 0;
+  const float4* row4 = reinterpret_cast<const float4*>(row);
+  for (int i = threadIdx.x; i < nv4; i += 256) {
+    float4 v = row4[i];
+    bad |= nonfinite(v.x) | nonfinite(v.y) | nonfinite(v.z) | nonfinite(v.w);
+    top2_push(t, v.x, 4 * i);
+    top2_push(t, v.y, 4 * i + 1);
+    top2_push(t, v.z, 4 * i + 2);
+    top2_push(t, v.w, 4 * i + 3);
+  }
+  for (int i = nv4 * 4 + threadIdx.x; i < V; i += 256) {
+    bad |= nonfinite(row[i]);
+    top2_push(t, row[i], i);
+  }
+  top2_block_finish(t, bad, amax, margin, flag);
+}
+
 void launch_argmax(const float* logits, int64_t row_stride, int rows, int V, int32_t* amax,
-                   float* margin, hipStream_t s) {
+                   float* margin, int32_t* flag, hipStream_t s) {
   if (rows <= 0) return;
-  hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(256), 0, s, logits, row_stride, V, amax, margin);
+  hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(256), 0, s, logits, row_stride, V, amax, margin, flag);
+}
+
+// The same verdict from per-(row, 64-feature group) candidates that the LM-head GEMM's epilogue left instead of
+// logits: part[r][g] = (top-1 value, its id, top-2 value, non-finite flag) as four 32-bit words.  The merge rule
+// does not depend on the order, so the result equals argmax_kernel's on the materialised row bit for bit.
+__global__ __launch_bounds__(256) void top2_reduce_kernel(const uint4* __restrict__ part, int groups,
+                                                          int32_t* __restrict__ amax, float* __restrict__ margin,
+                                                          int32_t* __restrict__ flag) {
+  const uint4* row = part + (int64_t)blockIdx.x * groups;
+  Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
+  int bad = 0;
+  for (int g = threadIdx.x; g < groups; g += 256) {
+    const uint4 p = row[g];
+    Top2 o = {__uint_as_float(p.x), (int)p.y, __uint_as_float(p.z)};
+    top2_merge(t, o);
+    bad |= (int)p.w;
+  }
+  top2_block_finish(t, bad, amax, margin, flag);
+}
+
+void launch_top2_reduce(const void* part, int groups, int rows, int32_t* amax, float* margin, int32_t* flag,
+                        hipStream_t s) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(top2_reduce_kernel, dim3(rows), dim3(256), 0, s, reinterpret_cast<const uint4*>(part), groups,
+                     amax, margin, flag);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -376,8 +420,10 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const int32_t* __restri
                                                          const int32_t* __restrict__ parent,
                                                          const int32_t* __restrict__ depth,
                                                          const int32_t* __restrict__ seq_n,
-                                                         const int32_t* __restrict__ amax, int n_step,
+                                                         const int32_t* __restrict__ amax,
+                                                         const int32_t* __restrict__ row_flag, int n_step,
                                                          int mode, int32_t* __restrict__ out_n,
+                                                         int32_t* __restrict__ out_flag,
                                                          int32_t* __restrict__ out_path,
                                                          int32_t* __restrict__ out_tok, int stride) {
   int b = blockIdx.x;
@@ -386,6 +432,19 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const int32_t* __restri
   const int32_t* par = parent + (int64_t)b * n_step;
   const int32_t* dep = depth + (int64_t)b * n_step;
   const int32_t* am = amax + (int64_t)b * n_step;
+  // a step with a non-finite logit at a real node of any sequence has no verdict: every sequence gets path
+  // length 0 (nothing is compacted) and its flag raised
+  int bad = 0;
+  for (int b2 = 0; b2 < gridDim.x; ++b2)
+    for (int i = threadIdx.x; i < seq_n[b2]; i += 64) bad |= row_flag[(int64_t)b2 * n_step + i];
+  bad = __any(bad != 0);
+  if (bad) {
+    if (threadIdx.x == 0) {
+      out_n[b] = 0;
+      out_flag[b] = 1;
+    }
+    return;
+  }
   int best = -1;  // key = depth * 1024 + (1023 - node)
   if (mode == 1) {
     best = (n - 1) * 1024 + (1023 - (n - 1));
@@ -422,13 +481,14 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const int32_t* __restri
     }
     acc[len - 1] = am[end];
     out_n[b] = len;
+    out_flag[b] = 0;
   }
 }
 
-void launch_accept_walk(const StepMeta& m, const int32_t* amax, int mode, int32_t* out_n,
-                        int32_t* out_path, int32_t* out_tok, int stride, hipStream_t s) {
+void launch_accept_walk(const StepMeta& m, const int32_t* amax, const int32_t* row_flag, int mode, int32_t* out_n,
+                        int32_t* out_flag, int32_t* out_path, int32_t* out_tok, int stride, hipStream_t s) {
   hipLaunchKernelGGL(accept_walk_kernel, dim3(m.batch), dim3(64), 0, s, m.token, m.parent, m.depth,
-                     m.seq_n, amax, m.n_step, mode, out_n, out_path, out_tok, stride);
+                     m.seq_n, amax, row_flag, m.n_step, mode, out_n, out_flag, out_path, out_tok, stride);
 }
 
 }  // namespace ded

@@ -88,6 +88,8 @@ def test_init_rejects_bad_arguments_before_touching_the_device(b):
     assert b.lib().ded_accept(None, 0, None, None, None, None) == b.DED_EINVAL
     assert b.lib().ded_verify_step(None, 1, None, None, None, None, None) == b.DED_EINVAL
     assert "tree" in b.ded_strerror(b.DED_ETREE)
+    assert "NaN" in b.ded_strerror(b.DED_ENONFINITE) and b.DED_ENONFINITE == -8
+    assert b.ded_strerror(-99) == "unknown error"
 
 
 # ---------------------------------------------------------------------------------------------

@@ -489,6 +489,133 @@ def test_zero_layer_bf16_gemm_path():
     ver.close()
 
 
+@pytest.mark.parametrize("shape", ["ragged-vocab", "32000", "large-rows"])
+def test_fused_argmax_equals_argmax_of_materialised_logits(shape):
+    """Without a logits request the LM-head GEMM hands the argmax its per-tile candidates and the [rows][vocab]
+    logits never reach memory; with one they are written and reduced by the stand-alone kernel.  Tokens and
+    margins must be equal bit for bit (the merge rule is order-independent), on a vocabulary with a ragged last
+    feature group, on the benchmark's vocabulary, and through the large-row GEMM (batched trees, split-K)."""
+    if shape == "ragged-vocab":
+        cfg, batch, nodes = di.ModelConfig("t2-a", 1, 256, 2, 2, 128, 128, 1008, dtype="bf16"), 2, 40
+    elif shape == "32000":
+        cfg, batch, nodes = di.ModelConfig("t2-b", 1, 512, 4, 4, 128, 256, 32000, dtype="bf16"), 1, 64
+    else:
+        cfg, batch, nodes = di.ModelConfig("t2-c", 1, 512, 4, 2, 128, 256, 4112, dtype="bf16"), 4, 128
+    w = di.make_weights(cfg, seed=21, gain_jitter=0.1, std=0.05)
+    # duplicate LM-head rows make exact ties (margin 0, lowest id must win) part of the comparison
+    w["lm_head"][17] = w["lm_head"][3]
+    w["lm_head"][cfg.vocab - 1] = w["lm_head"][cfg.vocab - 70]
+    ver = _verifier(cfg, w, max_batch=batch, kv_capacity=64 + nodes, max_nodes=nodes)
+    parents = [di.random_tree(nodes - 3 * b, None, seed=30 + b) for b in range(batch)]
+    tokens = [di.zipf_tokens(cfg.vocab, nodes - 3 * b, seed=40 + b) for b in range(batch)]
+    ver.verify_step([0] * batch, parents, tokens)  # fused
+    a_f, m_f = ver.get_argmax()
+    acc_f = ver.accept(mode=0)
+    logits = ver.verify_step([0] * batch, parents, tokens, want_logits=True).cpu().numpy()  # materialised
+    a_m, m_m = ver.get_argmax()
+    acc_m = ver.accept(mode=0)
+    assert np.array_equal(a_f, a_m) and np.array_equal(m_f, m_m) and acc_f == acc_m
+    ties = 0
+    for b in range(batch):
+        n = len(parents[b])
+        assert (a_f[b, :n] == np.argmax(logits[b, :n], axis=1)).all()
+        top2 = np.partition(logits[b, :n], -2, axis=1)[:, -2:]
+        assert np.array_equal(m_f[b, :n], top2[:, 1] - top2[:, 0])
+        ties += int((m_f[b, :n] == 0).sum())
+    print(f"fused argmax [{shape}]: equal to the materialised one on {sum(len(p) for p in parents)} nodes ({ties} exact ties)")
+    ver.close()
+    if shape != "ragged-vocab":
+        return
+    # exact ties at the top of EVERY row: the vocabulary's second half repeats the first (partners 504 ids apart,
+    # i.e. in different feature groups and wavefronts), then neighbours repeat each other (partners inside one
+    # lane's four features).  The lowest id must win and the margin must be exactly zero, fused and materialised.
+    for variant in ("halves", "neighbours"):
+        w2 = dict(w)
+        lm = w["lm_head"].copy()
+        if variant == "halves":
+            lm[504:] = lm[:504]
+        else:
+            lm[1::2] = lm[0::2]
+        w2["lm_head"] = lm
+        ver = _verifier(cfg, w2, max_batch=batch, kv_capacity=64 + nodes, max_nodes=nodes)
+        ver.verify_step([0] * batch, parents, tokens)
+        a_f, m_f = ver.get_argmax()
+        ver.accept(mode=0)
+        ver.verify_step([0] * batch, parents, tokens, want_logits=True)
+        a_m, m_m = ver.get_argmax()
+        ver.accept(mode=0)
+        assert np.array_equal(a_f, a_m) and np.array_equal(m_f, m_m)
+        for b in range(batch):
+            n = len(parents[b])
+            assert (m_f[b, :n] == 0).all()
+            assert (a_f[b, :n] < 504).all() if variant == "halves" else (a_f[b, :n] % 2 == 0).all()
+        ver.close()
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_non_finite_logits_are_reported_not_walked(dtype):
+    """A token whose embedding lies outside the half-precision operand range (bf16 storage holds it, the f16
+    matrix-core operands do not) or is infinite (fp32) makes the logits of its node NaN: ded_get_argmax, ded_sample
+    and ded_accept return DED_ENONFINITE instead of a token, nothing of that sequence is kept, and the next,
+    finite step on the same context is as correct as any other."""
+    from paper_2407_12021_amd import binding as B
+    hd = 128 if dtype == "bf16" else 32
+    cfg = di.ModelConfig("nf-" + dtype, 2, 128, 2, 1, hd, 128, 320, dtype=dtype)
+    w = di.make_weights(cfg, seed=12, gain_jitter=0.1)
+    poison = 77
+    if dtype == "bf16":
+        w["emb"][poison] = di.f32_to_bf16_bits(np.full(cfg.d_model, 3.0e38, np.float32))
+    else:
+        w["emb"][poison] = np.inf
+    prefix = di.zipf_tokens(cfg.vocab, 40, seed=3)
+    prefix = np.where(prefix == poison, poison + 1, prefix).astype(np.int32)
+    ver = _verifier(cfg, w, max_batch=2, kv_capacity=192, max_nodes=24)
+    gpu_prefill(ver, [prefix, prefix], seq_count=2)
+    _, pk, pv = oracle.prefill(cfg, w, prefix)
+    parent = di.random_tree(20, None, seed=5)
+    clean = di.zipf_tokens(cfg.vocab, 20, seed=6)
+    clean = np.where(clean == poison, poison + 1, clean).astype(np.int32)
+    bad = clean.copy()
+    bad[11] = poison
+    P = len(prefix)
+    for use_sample in (False, True):
+        ver.verify_step([P, P], [parent, parent], [clean, bad])
+        rc, _, _ = B.ded_get_argmax(ver.ctx, 2, ver.max_nodes)
+        assert rc == B.DED_ENONFINITE
+        if use_sample:
+            with pytest.raises(B.DedError) as e:
+                ver.sample(1.0, 0.9, [np.full(20, 0.5, np.float32)] * 2)
+            assert e.value.code == B.DED_ENONFINITE
+        rc, _, nacc, _, newp = B.ded_accept(ver.ctx, 0, 2, ver.max_nodes)
+        assert rc == B.DED_ENONFINITE and nacc.tolist() == [0, 0] and newp.tolist() == [0, 0]  # nothing written
+        rc, *_ = B.ded_accept(ver.ctx, 0, 2, ver.max_nodes)
+        assert rc == B.DED_ESTATE  # the step was consumed
+    # the poisoned step kept nothing of either sequence: a finite step from the same prefix is right in both.  Its
+    # tree is SMALLER, so the slot that held the NaN key / value lies in the dead tail of the tile that the
+    # attention kernel still fetches: it must have been zeroed.
+    small, n2 = di.random_tree(9, None, seed=7), 9
+    want = ver.verify_step([P, P], [small, small], [clean[:n2], clean[:n2]], want_logits=True).cpu().numpy()
+    ref, _, _ = oracle.verify_tree(cfg, w_finite(w, poison), small, clean[:n2], pk, pv)
+    for b in range(2):
+        assert np.abs(want[b, :n2] - ref).max() <= TOL[dtype]
+    a_gpu, _ = ver.get_argmax()
+    acc, path, newp = ver.accept(mode=0)
+    for b in range(2):
+        acc2, path2 = oracle.accept_walk(small, clean[:n2], a_gpu[b, :n2])
+        assert acc[b] == acc2 and path[b] == path2 and newp[b] == P + len(path2)
+    ver.close()
+
+
+def w_finite(w, row):
+    """The same weights with the poisoned embedding row zeroed (the oracle widens whole matrices; the row is never
+    looked up in the finite step)."""
+    out = dict(w)
+    emb = w["emb"].copy()
+    emb[row] = 0
+    out["emb"] = emb
+    return out
+
+
 SAMPLE_SLACK = 1e-4  # fp32 sums of up to 32000 weights against fp64: decisions closer than this to a boundary may flip
 
 
