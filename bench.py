@@ -6,11 +6,15 @@ with tree-masked attention, LM head, per-node argmax) + ded_accept (approval wal
 result download) on the Llama-2-7B shape with a 1024-token prefix and a 64-node draft tree
 (synthetic random-init bf16 weights, Zipf prefix, tri-gram-seeded tree; everything resident in HBM).
 
-Prints ONE JSON line.  `value` = verify steps/s.  Extra fields: verified tokens/s (raw tri-gram trees
-and with planted acceptance), per-kernel-class times, the roofline of the dominant kernel (the
-weight-streaming GEMM), a second roofline object for the tree-attention kernel measured on the
-attention-only configuration (32 heads x 128, 4096-key prefix, 64 nodes, rotating KV buffers), and
-the CPU oracle timed on a bounded sample.
+Prints ONE JSON line.  `value` = verify steps/s = 1 / median step time, the median taken over at least 50
+steps (and at least one second of them) after at least 10 warm-up steps, each step bracketed by HIP events on
+the library's stream; the wall-clock median and mean per step are printed beside it.  Extra fields: verified
+tokens/s (raw tri-gram trees and with planted acceptance), per-kernel-class times, the roofline of the dominant
+kernel (the gate/up weight-streaming GEMM) and of all GEMMs, measured ceilings of the same run (a plain streaming
+read, a large library GEMM) with every fraction also against them, tree attention on the attention-only
+configuration (split-KV kernel plus merge kernel), the matrix-core-bound batched shapes, the batched
+configurations c4 and c5 at their own depth, the paper's own tree shape (24 candidates of 4 tokens: up to 97
+rows), and the CPU oracle timed on one whole step of the benchmark workload.
 """
 import argparse
 import json
@@ -22,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+GEMM_CLASSES = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head"]
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
 # HBM traffic per launch, KiB, as read by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --pmc-mode`
@@ -87,21 +92,75 @@ def planted_trees(di, ver, wl, prefix, parent, token, seed):
     return trees
 
 
-def time_steps(ver, P, parent, tokens_list, steps, warmup):
+def time_steps(step, min_steps, warmup, min_seconds=1.0, max_steps=2000):
+    """step(i) runs one whole verification step (ded_verify_step + ded_accept, which synchronises) and returns the
+    number of tokens it committed.  Every timed step sits between two HIP events recorded on the library's stream
+    (torch's current stream) and between two host clock readings.  At least `min_steps` steps and `min_seconds`
+    of them are timed after `warmup` untimed ones."""
+    import statistics
     import torch
-    n_tok = 0
     for i in range(warmup):
-        ver.verify_step([P], [parent], [tokens_list[i % len(tokens_list)]])
-        ver.accept(mode=0)
+        step(i)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        ver.verify_step([P], [parent], [tokens_list[i % len(tokens_list)]])
-        acc, _, _ = ver.accept(mode=0)
-        n_tok += len(acc[0])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    return dt, n_tok
+    ev_ms, wall_ms, n_tok, i = [], [], 0, 0
+    while i < max_steps and (i < min_steps or sum(wall_ms) < 1e3 * min_seconds):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        n_tok += step(warmup + i)
+        e1.record()
+        e1.synchronize()
+        wall_ms.append((time.perf_counter() - t0) * 1e3)
+        ev_ms.append(e0.elapsed_time(e1))
+        i += 1
+    return {"steps": i, "tokens": n_tok, "event_ms_median": statistics.median(ev_ms),
+            "wall_ms_median": statistics.median(wall_ms), "wall_ms_mean": sum(wall_ms) / i,
+            "event_ms_p10": sorted(ev_ms)[i // 10], "event_ms_p90": sorted(ev_ms)[(9 * i) // 10]}
+
+
+def measured_ceilings():
+    """What this chip sustains in this run, by the simplest possible kernels: (1) a plain streaming read of 2 GiB
+    (the library's probe kernel, 16 bytes per lane), (2) a large square bf16 GEMM from the vendor library
+    (8192^3 through torch.matmul).  The streaming kernels are reported against (1), the matrix-core-bound ones
+    against (2), beside the published peaks."""
+    import statistics
+    import torch
+    from paper_2407_12021_amd import binding as B
+    n = 2 << 30
+    buf = torch.empty(n, dtype=torch.uint8, device="cuda")
+    buf.random_(0, 255)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    times = []
+    for i in range(12):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rc = B.ded_probe_stream_read(buf.data_ptr(), n, sink.data_ptr(), st)
+        e1.record()
+        e1.synchronize()
+        assert rc == 0
+        if i >= 2:
+            times.append(e0.elapsed_time(e1))
+    read_gbs = n / (statistics.median(times) * 1e-3) / 1e9
+    del buf
+    m = 8192
+    a = torch.randn(m, m, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(m, m, device="cuda", dtype=torch.bfloat16)
+    times = []
+    for i in range(12):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        c = a @ b
+        e1.record()
+        e1.synchronize()
+        if i >= 2:
+            times.append(e0.elapsed_time(e1))
+    gemm_tflops = 2.0 * m ** 3 / (statistics.median(times) * 1e-3) / 1e12
+    del a, b, c
+    torch.cuda.empty_cache()
+    return {"stream_read_gbs": read_gbs, "stream_read": "2 GiB, 16 B per lane, library probe kernel, median of 10",
+            "library_gemm_tflops": gemm_tflops, "library_gemm": "bf16 8192 x 8192 x 8192 via torch.matmul, median of 10",
+            "hbm_peak_gbs": HBM_PEAK_GBS, "mfma_peak_tflops": MFMA_BF16_PEAK_TFLOPS}
 
 
 def decode_loop_bench(di, ver, wl, prefix, root, n_new=48, seed=2):
@@ -218,17 +277,20 @@ def attention_only_bench(di, iters=40):
     prof = ver.profile_read()
     ver.profile(False)
     ver.close()
-    ms, n = prof["tree_attention"]
-    ms_merge, _ = prof["attention_merge"]
+    ms, n = prof["tree_attention"]  # one bracket around the whole operation: split-KV kernel + merge kernel
     keys = wl.prefix_len + wl.n_nodes
-    kv_bytes = 2 * keys * 32 * 128 * 2            # K and V, bf16, every key of every kv head once
+    kv_bytes = 2 * keys * 32 * 128 * 2            # K and V, 2 bytes each, every key of every kv head once
     q_o_bytes = 2 * wl.n_nodes * 32 * 128 * 2      # q in, o out
     alg = kv_bytes + q_o_bytes
     us = ms / n * 1e3
-    return {"bound": "hbm", "kernel": "tree_attn_partial_kernel", "workload": "c2 attention-only",
-            "achieved": alg / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": pmc_bytes("tree_attention_c2"),
-            "us_per_launch": us, "merge_us_per_launch": ms_merge / n * 1e3, "algorithmic_bytes": alg}
+    whole = alg / (us * 1e-6) / 1e9
+    return {"bound": "hbm", "kernel": "tree_attn_tiled_kernel + tree_attn_merge_kernel (the whole attention operation)",
+            "workload": "c2 attention-only: 32 heads x 128, 4096-key prefix, 64-node tree of depth 8, 8 rotating K/V sets",
+            "achieved": whole, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": whole / HBM_PEAK_GBS,
+            "traffic": pmc_bytes("tree_attention_c2"),
+            "time_base": "one HIP-event bracket around the two launches of the operation (ded_profile_*); per-kernel "
+                         "durations: profiles/c2_tree_attention_kernel_stats.md",
+            "us_per_launch": us, "algorithmic_bytes": alg}
 
 
 def large_rows_bench(di, steps=8):
@@ -279,6 +341,55 @@ def large_rows_bench(di, steps=8):
             "frac": best["executed_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "cases": out}
 
 
+STEP_LOWER_BOUND_MS = {"c3": 1.72, "c4": 6.2, "c5": 19.4}  # weight / cache bytes at 8 TB/s or matrix flops at 2.5 PFLOP/s
+
+
+def batched_config_bench(di, name, min_steps):
+    """One of the batched configurations at its own depth and size (c4: 13B shape, 40 layers, batch 4, prefix 2048,
+    128-node trees; c5: Llama-3-8B shape, 32 layers, batch 8, prefix 16384, 256-node trees): random-init weights,
+    prefix computed by chunked prefill, then the tree step timed like the headline (event median)."""
+    import torch
+    from paper_2407_12021_amd import Verifier
+    wl = di.WORKLOADS[name]
+    cfg = wl.model
+    t0 = time.perf_counter()
+    w = di.make_weights(cfg, seed=0, threads=16)
+    B, N = wl.batch, wl.n_nodes
+    ver = Verifier(cfg, w, max_batch=B, kv_capacity=wl.prefix_len + N + wl.depth + 2, max_nodes=N)
+    del w
+    seqs = [di.workload_tree(wl, seed=0, seq=b) for b in range(B)]
+    P = wl.prefix_len
+    for s0 in range(0, P, N):
+        n = min(N, P - s0)
+        ver.verify_step([s0] * B, [di.chain_tree(n)] * B, [q[0][s0:s0 + n] for q in seqs])
+        ver.accept(mode=1)
+    torch.cuda.synchronize()
+    log(f"{name}: weights, init and prefill {time.perf_counter() - t0:.1f} s")
+    parents, tokens = [q[1] for q in seqs], [q[2] for q in seqs]
+
+    def step(i):
+        ver.verify_step([P] * B, parents, tokens)
+        acc, _, _ = ver.accept(mode=0)
+        return sum(len(a) for a in acc)
+
+    r = time_steps(step, min_steps, 3, min_seconds=0.5)
+    ver.profile(True)
+    for i in range(3):
+        step(i)
+    prof = ver.profile_read()
+    ver.profile(False)
+    ver.close()
+    ms = r["event_ms_median"]
+    rows = B * N
+    flops = 2.0 * rows * gemm_weight_elems(cfg)
+    return {"workload": f"{name}: {cfg.name}, {cfg.n_layers} layers, batch {B}, prefix {P}, {N}-node trees",
+            "steps_per_s": 1e3 / ms, "ms_per_step": ms, "wall_ms_per_step_median": r["wall_ms_median"],
+            "timed_steps": r["steps"], "verified_tokens_per_s_raw_trees": r["tokens"] / r["steps"] * 1e3 / ms,
+            "step_lower_bound_ms": STEP_LOWER_BOUND_MS[name], "frac_of_lower_bound": STEP_LOWER_BOUND_MS[name] / ms,
+            "projection_useful_tflops": flops / (sum(prof[c][0] for c in GEMM_CLASSES) / 3 * 1e-3) / 1e12,
+            "kernel_ms_per_step": {k: round(v[0] / 3, 3) for k, v in prof.items() if v[1]}}
+
+
 def cpu_baseline(di, wl, parent, token):
     """The fp64 oracle as it stands, timed on one whole verification step of the benchmark workload (all 32 layers,
     64-row tree against a 1024-key prefix; random K/V stand in for the prefix: the oracle's time does not depend
@@ -316,6 +427,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn", action="store_true")
     ap.add_argument("--no-large-rows", action="store_true")
+    ap.add_argument("--no-batched", action="store_true", help="skip the c4 / c5 step timings (26 GB and 15 GB of weights)")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: a 1 GiB torch copy (calibration), 2 verify steps and 2 attention-only "
                          "launches, nothing else")
@@ -340,7 +452,9 @@ def main():
     log(f"weights: {time.perf_counter() - t0:.1f} s")
     prefix, parent, token = di.workload_tree(wl, seed=0)
     t0 = time.perf_counter()
-    ver = Verifier(cfg, w, max_batch=1, kv_capacity=wl.prefix_len + wl.n_nodes + wl.depth + 2, max_nodes=wl.n_nodes)
+    # max_nodes 128: the same context also runs the 97-row tree of the paper's shape; a step's kernels are shaped
+    # by the step's own node count (64 here), not by the maximum
+    ver = Verifier(cfg, w, max_batch=1, kv_capacity=wl.prefix_len + 128 + wl.depth + 2, max_nodes=128)
     del w
     log(f"upload + init: {time.perf_counter() - t0:.1f} s")
     P = len(prefix)
@@ -362,48 +476,78 @@ def main():
         return
     planted = planted_trees(di, ver, wl, prefix, parent, token, seed=1)
 
+    def step_planted(i):
+        ver.verify_step([P], [parent], [planted[i % len(planted)]])
+        acc, _, _ = ver.accept(mode=0)
+        return len(acc[0])
+
+    def step_raw(i):
+        ver.verify_step([P], [parent], [token])
+        acc, _, _ = ver.accept(mode=0)
+        return len(acc[0])
+
     # headline: planted acceptance (kernel time does not depend on the acceptance length)
-    dt, n_tok = time_steps(ver, P, parent, planted, args.steps, args.warmup)
-    dt_raw, n_tok_raw = time_steps(ver, P, parent, [token], max(5, args.steps // 4), 1)
-    raw_steps = max(5, args.steps // 4)
+    head = time_steps(step_planted, max(args.steps, 50), max(args.warmup, 10))
+    raw = time_steps(step_raw, 20, 2, min_seconds=0.2)
+    ms_step = head["event_ms_median"]
+
+    # the paper's own tree shape (Appendix F.1: n = 24 candidates of l = 4 tokens): the pseudo-sequence has up to
+    # 1 + 24 * 4 = 97 rows when no two candidates share a prefix; that worst case is timed here
+    g = np.random.default_rng(4)
+    cands = [[int(x) for x in g.choice(cfg.vocab, size=4, replace=False)] for _ in range(24)]
+    firsts = g.choice(cfg.vocab, size=24, replace=False)
+    for c, f in zip(cands, firsts):
+        c[0] = int(f)
+    from paper_2407_12021_amd import binding as B
+    rc, parent97, token97, _ = B.ded_build_tree(int(token[0]), cands, 128)
+    assert rc == 0 and len(parent97) == 97
+
+    def step_paper(i):
+        ver.verify_step([P], [parent97], [token97])
+        acc, _, _ = ver.accept(mode=0)
+        return len(acc[0])
+
+    paper = time_steps(step_paper, 50, 5, min_seconds=0.3)
+    paper_shape = {"candidates": 24, "tokens_per_candidate": 4, "nodes": 97, "ms_per_step": paper["event_ms_median"],
+                   "steps_per_s": 1e3 / paper["event_ms_median"],
+                   "ratio_to_64_node_step": paper["event_ms_median"] / ms_step,
+                   "verified_tokens_per_s_at_paper_accept_2.4": 2.4 * 1e3 / paper["event_ms_median"]}
 
     decode = decode_loop_bench(di, ver, wl, prefix, int(token[0]))
 
     # stochastic approval (temperature 0.8, top-p 0.9): the extra cost of sampling the model's token at 64 nodes
     g = np.random.default_rng(3)
-    n_st = 10
 
-    def sampled_steps(n):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(n):
-            ver.verify_step([P], [parent], [planted[i % len(planted)]])
-            ver.sample(0.8, 0.9, [g.random(len(parent)).astype(np.float32)])
-            ver.accept(mode=0)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+    def step_sampled(i):
+        ver.verify_step([P], [parent], [planted[i % len(planted)]])
+        ver.sample(0.8, 0.9, [g.random(len(parent)).astype(np.float32)])
+        acc, _, _ = ver.accept(mode=0)
+        return len(acc[0])
 
-    sampled_steps(2)
-    dt_st = sampled_steps(n_st)
-    ver.profile(True)
-    sampled_steps(3)
-    prof_st = ver.profile_read()
-    ver.profile(False)
-    stochastic = {"temperature": 0.8, "top_p": 0.9, "steps_per_s": n_st / dt_st, "ms_per_step": dt_st / n_st * 1e3,
-                  "sample_kernel_us": prof_st["sample_top_p"][0] / max(prof_st["sample_top_p"][1], 1) * 1e3}
-
-    # per-kernel-class times (separate pass: event brackets add overhead)
+    # per-kernel-class times of the plain step first (separate pass: event brackets add ~2 us per launch); the
+    # sampled steps come last because a context that has sampled keeps materialising its logits
     ver.profile(True)
     prof_steps = 5
     for i in range(prof_steps):
-        ver.verify_step([P], [parent], [planted[i % len(planted)]])
-        ver.accept(mode=0)
+        step_planted(i)
     prof = ver.profile_read()
     ver.profile(False)
+    st = time_steps(step_sampled, 20, 3, min_seconds=0.2)
+    ver.profile(True)
+    for i in range(3):
+        step_sampled(i)
+    prof_st = ver.profile_read()
+    ver.profile(False)
+    stochastic = {"temperature": 0.8, "top_p": 0.9, "steps_per_s": 1e3 / st["event_ms_median"],
+                  "ms_per_step": st["event_ms_median"],
+                  "sample_kernel_us": prof_st["sample_top_p"][0] / max(prof_st["sample_top_p"][1], 1) * 1e3}
     ver.close()
-    gemm_classes = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head"]
-    gemm_ms = sum(prof[c][0] for c in gemm_classes) / prof_steps
-    gemm_launches = sum(prof[c][1] for c in gemm_classes) // prof_steps
+    del ver
+    torch.cuda.empty_cache()
+    ceil = measured_ceilings()
+
+    gemm_ms = sum(prof[c][0] for c in GEMM_CLASSES) / prof_steps
+    gemm_launches = sum(prof[c][1] for c in GEMM_CLASSES) // prof_steps
     w_bytes = 2.0 * gemm_weight_elems(cfg)
     gemm_gbs = w_bytes / (gemm_ms * 1e-3) / 1e9
     gemm_tflops = 2.0 * wl.n_nodes * gemm_weight_elems(cfg) / (gemm_ms * 1e-3) / 1e12
@@ -413,18 +557,26 @@ def main():
     gu_bytes = 2.0 * 2 * cfg.d_ffn * cfg.d_model
     gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9
     full_model = cfg.n_layers == wl.model.n_layers
-    per_launch = {c: prof[c][0] / max(prof[c][1], 1) * 1e3 for c in gemm_classes}
-    gemm_traffic_step = (sum(pmc_bytes(c) for c in gemm_classes[:4]) * cfg.n_layers + pmc_bytes("gemm_lm_head")
+    per_launch = {c: prof[c][0] / max(prof[c][1], 1) * 1e3 for c in GEMM_CLASSES}
+    gemm_traffic_step = (sum(pmc_bytes(c) for c in GEMM_CLASSES[:4]) * cfg.n_layers + pmc_bytes("gemm_lm_head")
                          if full_model else None)
+    step_bytes = w_bytes + 2.0 * 2 * (P + wl.n_nodes) * cfg.n_kv_heads * cfg.head_dim * cfg.n_layers
+    time_base = ("HIP-event brackets around each launch on the library's stream in a separate 5-step pass "
+                 "(ded_profile_*; ~2 us of bracket per launch included); kernel-only durations: "
+                 "profiles/c3_verify_step_kernel_stats.md")
 
     out = {
         "metric": "tree-verify steps/s at 7B shape (64-node tree, 1024-token prefix, batch 1)",
-        "value": args.steps / dt,
+        "value": 1e3 / ms_step,
         "unit": "verify steps/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": dt / args.steps * 1e3,
+        "ms_per_step": ms_step,
+        "timing": {"what": "median over timed_steps steps, each between two HIP events on the library's stream, after "
+                           "warmup_steps untimed steps", "timed_steps": head["steps"], "warmup_steps": max(args.warmup, 10),
+                   "event_ms_p10": head["event_ms_p10"], "event_ms_p90": head["event_ms_p90"],
+                   "wall_ms_per_step_median": head["wall_ms_median"], "wall_ms_per_step_mean": head["wall_ms_mean"]},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -434,33 +586,51 @@ def main():
                                "64-node tri-gram-seeded tree of depth 6, batch 1"
                                + (f" [DEBUG: {args.layers} layers]" if args.layers else ""),
                    "n_layers": cfg.n_layers, "prefix_len": P, "n_nodes": wl.n_nodes, "batch": 1},
-        "verified_tokens_per_s": n_tok / dt,
-        "mean_accepted_per_step": n_tok / args.steps,
+        "verified_tokens_per_s": head["tokens"] / head["steps"] * 1e3 / ms_step,
+        "mean_accepted_per_step": head["tokens"] / head["steps"],
         "acceptance": "planted: one branch carries the model's own continuation for m~Geom tokens",
-        "raw_trigram_tree": {"steps_per_s": raw_steps / dt_raw, "verified_tokens_per_s": n_tok_raw / dt_raw,
-                             "mean_accepted_per_step": n_tok_raw / raw_steps},
+        "step_hbm": {"algorithmic_bytes_per_step": step_bytes, "achieved_gbs": step_bytes / (ms_step * 1e-3) / 1e9,
+                     "frac_of_peak": step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "frac_of_measured_stream_read": step_bytes / (ms_step * 1e-3) / 1e9 / ceil["stream_read_gbs"],
+                     "step_lower_bound_ms": STEP_LOWER_BOUND_MS["c3"]},
+        "raw_trigram_tree": {"steps_per_s": 1e3 / raw["event_ms_median"],
+                             "verified_tokens_per_s": raw["tokens"] / raw["steps"] * 1e3 / raw["event_ms_median"],
+                             "mean_accepted_per_step": raw["tokens"] / raw["steps"]},
+        "paper_shape": paper_shape,
         "decode_loop": decode,
         "stochastic_approval": stochastic,
         "kernel_ms_per_step": kernels_ms,
+        "ceilings": ceil,
         "roofline": {"bound": "hbm",
                      "kernel": "gate/up projection GEMM with SiLU*up epilogue (gemm_wide_kernel, 3 feature groups per "
                                "workgroup, 2 activation planes, split-K 2): 22016 x 4096 bf16 weights per launch",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
+                     "frac_of_measured_stream_read": gu_gbs / ceil["stream_read_gbs"],
                      "traffic": pmc_bytes("gemm_gate_up") if full_model else None,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --pmc-mode` "
+                                       "(profiles/c3_verify_step_hbm_traffic_pmc.md), not re-measured in this run",
+                     "time_base": time_base,
                      "avg_launch_us": gu_us, "algorithmic_bytes_per_launch": gu_bytes,
-                     "launches_per_step": cfg.n_layers, "share_of_step": gu_us * 1e-3 * cfg.n_layers / (dt / args.steps * 1e3)},
+                     "launches_per_step": cfg.n_layers, "share_of_step": gu_us * 1e-3 * cfg.n_layers / ms_step},
         "roofline_all_gemms": {"bound": "hbm", "kernel": "all projection GEMMs of a step (QKV, O, gate/up, down, LM head)",
                                "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
+                               "frac_of_measured_stream_read": gemm_gbs / ceil["stream_read_gbs"],
                                "traffic_per_step": gemm_traffic_step, "launches_per_step": int(gemm_launches),
                                "avg_launch_us": gemm_ms * 1e3 / max(gemm_launches, 1),
                                "us_per_launch_by_class": {k: round(v, 2) for k, v in per_launch.items()},
                                "algorithmic_bytes_per_step": w_bytes, "mfma_tflops": gemm_tflops,
-                               "mfma_frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
+                               "mfma_frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS, "time_base": time_base},
     }
     if not args.no_attn:
-        out["roofline_tree_attention"] = attention_only_bench(di)
+        att = attention_only_bench(di)
+        att["frac_of_measured_stream_read"] = att["achieved"] / ceil["stream_read_gbs"]
+        out["roofline_tree_attention"] = att
     if not args.no_large_rows:
-        out["roofline_large_rows"] = large_rows_bench(di)
+        lr = large_rows_bench(di)
+        lr["frac_of_library_gemm"] = lr["achieved"] / ceil["library_gemm_tflops"]
+        out["roofline_large_rows"] = lr
+    if not args.no_batched:
+        out["batched_configs"] = {"c4": batched_config_bench(di, "c4", 20), "c5": batched_config_bench(di, "c5", 10)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(di, wl, parent, token)
     print(json.dumps(out), flush=True)

@@ -284,6 +284,13 @@ size_t ded_static_scratch_bytes(void);
 int ded_profile_enable(ded_ctx *ctx, int32_t on);
 int ded_profile_read(ded_ctx *ctx, int32_t cap, const char **names, double *total_ms, int64_t *launches);
 
+/* Measurement aid, not part of the method: one pass of plain 16-byte-per-lane reads over `bytes` of device
+ * memory (device_buffer 16-byte aligned; sink4: 4 bytes of device memory that the kernel may write),
+ * enqueued on hip_stream.  bytes / kernel time is the streaming-read rate this chip sustains, the
+ * ceiling that the weight- and cache-streaming kernels of the library are reported against.
+ * Errors: DED_EINVAL, DED_EHIP. */
+int ded_probe_stream_read(const void *device_buffer, size_t bytes, void *sink4, void *hip_stream);
+
 const char *ded_strerror(int code);
 
 #ifdef __cplusplus

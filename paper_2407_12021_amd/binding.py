@@ -22,7 +22,7 @@ DED_F32, DED_BF16 = 0, 1
 EXPORTS = [
     "ded_workspace_bytes", "ded_kv_layer_bytes", "ded_validate_tree", "ded_build_tree", "ded_verify_init", "ded_verify_free",
     "ded_verify_step", "ded_sample", "ded_accept", "ded_get_argmax", "ded_kv_store", "ded_kv_load", "ded_tree_attention",
-    "ded_tree_attention_static", "ded_static_scratch_bytes",
+    "ded_tree_attention_static", "ded_static_scratch_bytes", "ded_probe_stream_read",
     "ded_profile_enable", "ded_profile_read", "ded_strerror",
     "ded_trigram_create", "ded_trigram_free", "ded_trigram_count", "ded_trigram_finalize", "ded_trigram_adjust",
     "ded_trigram_lookup", "ded_trigram_size", "ded_draft_mcts",
@@ -119,6 +119,8 @@ def lib() -> C.CDLL:
             f.argtypes = [vp, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp]
         L.ded_static_scratch_bytes.restype = C.c_size_t
         L.ded_static_scratch_bytes.argtypes = []
+        L.ded_probe_stream_read.restype = C.c_int
+        L.ded_probe_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.ded_profile_enable.restype = C.c_int
         L.ded_profile_enable.argtypes = [vp, C.c_int32]
         L.ded_profile_read.restype = C.c_int
@@ -308,6 +310,10 @@ def ded_tree_attention_static(ctx, layer, prefix_len, n_nodes, parent, q_ptr, k_
 
 def ded_static_scratch_bytes() -> int:
     return int(lib().ded_static_scratch_bytes())
+
+
+def ded_probe_stream_read(buffer_ptr: int, nbytes: int, sink_ptr: int, stream_ptr: int) -> int:
+    return int(lib().ded_probe_stream_read(buffer_ptr, nbytes, sink_ptr, stream_ptr))
 
 
 def ded_profile_enable(ctx, on: bool) -> int:

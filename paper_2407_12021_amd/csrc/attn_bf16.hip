@@ -1,20 +1,20 @@
 // Tree-masked attention for the 16-bit path (f16 K/V cache, head_dim 128), split over the key axis.
 //
-// Work unit: (sequence, kv head, tile of 64 "virtual rows", key range).  The virtual rows of a kv head
-// are its G query heads x n_step tree rows (vr = g * n_step + node), so grouped-query heads share
-// every K/V byte that is fetched.  A workgroup of 4 wavefronts streams its key range in tiles of 64
-// keys: the K and V^T fragments of a tile (32 KiB, contiguous in the cache) are fetched with fully
-// coalesced 16-byte loads, parked in LDS (double buffered) and consumed by all four wavefronts, each
-// of which owns 16 of the 64 rows:
-//     S^T = K . Q^T           v_mfma_f32_16x16x32_f16, A = key fragment (LDS), B = query fragment (VGPR)
-//     online soft-max          per lane: 1 row, 16 keys of the tile; row max via two wavefront shuffles
-//     O^T += V^T . P^T         A = value fragment (LDS), B = probabilities straight from the S^T registers
-// The key rows of a 32-key group are interleaved inside the two 16-row tiles (see packk_index) so that
-// after the first product a lane holds 8 consecutive keys - exactly the B-operand slice the second
-// product needs, with no cross-lane traffic.  The ancestor mask is a per-row bitmask over tree slots;
-// tiles that lie entirely inside the prefix skip all mask work.
-// Each workgroup writes (running max, sum, unnormalised output) per row; a second kernel merges the
-// key ranges in a fixed order and writes the output as hi/lo f16 in PackX for the O projection.
+// Work unit: (sequence, kv head, tile of "virtual rows", key range).  The virtual rows of a kv head are its G
+// query heads x n_step tree rows (vr = g * n_step + node), so grouped-query heads share every K/V byte that is
+// fetched.  A workgroup streams its key range in tiles of 64 keys: the K and V^T fragments of a tile (32 KiB,
+// contiguous in the cache) are fetched with fully coalesced 16-byte loads, parked in LDS (double buffered) and
+// consumed by the wavefronts, each of which owns one or two blocks of 16 rows:
+//     S^T = K . Q^T           v_mfma_f32_16x16x32_f16, A = key fragment (LDS), B = query fragment (VGPR, hi + lo)
+//     online soft-max          per lane: 1 row, 8 keys of a 32-key chunk; row max via two wavefront shuffles
+//     O^T += V^T . P^T         A = value fragment (LDS), B = weights straight from the S^T registers
+//     l   += 1^T . P^T         the weights' sum, by the matrix cores as well (a row of ones)
+// The key rows of a 32-key group are interleaved inside the two 16-row tiles (see packk_index) so that after the
+// first product a lane holds 8 consecutive keys - exactly the B-operand slice the second product needs, with no
+// cross-lane traffic.  The ancestor mask is a per-row bitmask over tree slots; chunks that lie entirely inside
+// the prefix skip all mask work and take the short soft-max path (3 arithmetic instructions per score).
+// Each workgroup writes (running max, sum, unnormalised output) per row; a second kernel merges the key ranges
+// in a fixed order and writes the output as hi/lo f16 in PackX for the O projection.
 #include <algorithm>
 
 #include "bf16_layout.h"
@@ -28,221 +28,323 @@ constexpr int TILE = 64;         // keys per tile
 constexpr int TILE_U4 = 1024;    // uint4 units of one K (or V) tile: 64 keys * 128 dims * 2 B / 16
 constexpr float NEG_BIG = -1.0e30f;
 
-#ifdef DED_ATTN_TRACE
-__device__ unsigned long long* g_atrace = nullptr;  // [workgroup][4] wall-clock stamps (debug builds only)
-#define DED_ASTAMP(i)                                                                                         \
-  if (g_atrace && threadIdx.x == 0)                                                                           \
-    g_atrace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (i)] = wall_clock64();
-__device__ unsigned long long* g_aphase = nullptr;  // [workgroup][4] accumulated phase times of wave 0
-#define DED_APHASE_DECL unsigned long long ph_t = 0, ph_acc[4] = {0, 0, 0, 0};
-#define DED_APHASE_START ph_t = wall_clock64();
-#define DED_APHASE(i) { unsigned long long now_ = wall_clock64(); ph_acc[i] += now_ - ph_t; ph_t = now_; }
-#define DED_APHASE_FLUSH                                                                                      \
-  if (g_aphase && threadIdx.x == 0)                                                                           \
-    for (int i_ = 0; i_ < 4; ++i_)                                                                            \
-      g_aphase[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + i_] = ph_acc[i_];
-#else
-#define DED_ASTAMP(i)
-#define DED_APHASE_DECL
-#define DED_APHASE_START
-#define DED_APHASE(i)
-#define DED_APHASE_FLUSH
-#endif
+constexpr int CHUNK = 32;  // keys per chunk: the contraction length of one matrix instruction of the second product
 
-__global__ __launch_bounds__(256) void tree_attn_partial_kernel(
+// Online soft-max step of ONE row block (16 rows, one per lane & 15) over ONE 32-key chunk.  s[c2][i] is the raw
+// score (q . k, unscaled) of key key0 + quad * 8 + c2 * 4 + i against the lane's row.  Updates the row's running
+// maximum m_run (in units of score * scale * log2 e), returns the factor alpha by which everything accumulated
+// so far has to be multiplied, and the chunk's weights exp2(score' - m) as the f16 B operand of the second
+// product (the lane's eight consecutive keys).  The weights' sum is NOT formed here: the matrix cores add it up
+// (a row of ones in front of V^T), from the same rounded weights that they multiply with V.
+// plain = the chunk lies inside the prefix, every key is visible: max over the raw scores (the scale is
+// positive), then one fused multiply-add, one exponential and half a packed conversion (round towards zero; the
+// normaliser sees the same rounding) per score.  Otherwise the ancestor mask row (4 words over tree slots) decides
+// per key, and a row that has seen no visible key yet keeps weights of exactly zero.
+__device__ __forceinline__ void softmax_chunk(const f32x4_t (&s)[2], bool plain, int key0, int quad, int P, int T,
+                                              const uint64_t* mrow, float scale_log2e, float& m_run, float& alpha,
+                                              f16x8_t& pb) {
+  typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+  if (plain) {
+    float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx * scale_log2e);
+    alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    const float neg_m = -m_new;
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const float e0 = __builtin_amdgcn_exp2f(fmaf(s[j >> 2][j & 3], scale_log2e, neg_m));
+      const float e1 = __builtin_amdgcn_exp2f(fmaf(s[j >> 2][(j & 3) + 1], scale_log2e, neg_m));
+      const h2_t h = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(e0, e1));
+      pb[j] = h[0];
+      pb[j + 1] = h[1];
+    }
+  } else {
+    const uint64_t w0 = mrow[0], w1 = mrow[1], w2 = mrow[2], w3 = mrow[3];
+    float p[8];
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int key = key0 + quad * 8 + j;
+      const int tt = key - P;  // tree slot of this key (negative inside the prefix)
+      const int wi = tt >> 6;
+      const uint64_t word = wi == 0 ? w0 : wi == 1 ? w1 : wi == 2 ? w2 : w3;
+      const bool vis = (key < P) | ((key < T) & (bool)((word >> (tt & 63)) & 1ull));  // no short circuit: no branches
+      const float v = vis ? s[j >> 2][j & 3] * scale_log2e : NEG_BIG;
+      p[j] = v;
+      mx = fmaxf(mx, v);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const float e0 = p[j] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[j] - m_new) : 0.f;
+      const float e1 = p[j + 1] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[j + 1] - m_new) : 0.f;
+      const h2_t h = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(e0, e1));
+      pb[j] = h[0];
+      pb[j + 1] = h[1];
+    }
+  }
+}
+
+__device__ __forceinline__ f16x8_t f16_ones() {
+  f16x8_t v;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (_Float16)1.0f;
+  return v;
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Tiled kernel.  Work unit: (sequence, kv head, row tile, key range).  The K / V tiles of 64 keys (32 KiB,
+// contiguous in the cache) go global -> register -> LDS (double buffered, one barrier per tile) once per
+// workgroup.  A wavefront owns RBW row blocks of 16 rows.  With RBW = 2 a key or value fragment read from LDS
+// feeds two (four with the lo query plane) matrix instructions, queries take 32 / 64 registers and the output tile
+// 64, so two wavefronts still fit a SIMD and one's soft-max arithmetic runs under the other's matrix instructions.
+// NW wavefronts form NW / KS row groups x KS key groups: with KS = 1 every wavefront takes both 32-key chunks of
+// a tile; with KS = 2 a wavefront takes one chunk of every tile, so that few rows still spread over all
+// wavefronts, and the two key groups' (max, sum, O) are merged through LDS at the end, in key-group order.
+// Shapes in use (rows per workgroup tile = NW / KS * RBW * 16):
+//   64 rows  = 4 wavefronts x 16 rows, all keys each, two workgroups per CU: trees of one sequence, where a
+//              workgroup sees only a handful of tiles and a merge at its end would cost more than it saves;
+//   128 rows = 8 wavefronts as 4 row groups x 2 key groups;
+//   256 rows = 8 wavefronts x 32 rows, all keys each: many rows per kv head (batched trees, grouped-query heads),
+//              where the matrix cores bound the operation and LDS bytes per matrix instruction decide how busy
+//              they are.
+// Workgroup indices are remapped so that neighbours in (key range, row tile) order - which fetch the same K / V -
+// run on the same XCD and meet in its L2.
+// ------------------------------------------------------------------------------------------
+template <int QP, int NW, int KS, int RBW>
+__global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
     const uint4* __restrict__ qp, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
     float* __restrict__ part_o, float2* __restrict__ part_ml, const uint64_t* __restrict__ mask,
     const int32_t* __restrict__ seq_p, const int32_t* __restrict__ seq_n, int n_step, int H, int Hkv, int cap,
-    int n_splits, float scale_log2e) {
-  __shared__ uint4 lds[2][2 * TILE_U4];  // [buffer][K tile | V tile], 2 x 32 KiB
+    int n_splits, float scale_log2e, bf16_t* __restrict__ o_final, int RB_total) {
+  constexpr int NT = NW * 64;          // threads
+  constexpr int RG = NW / KS;          // row groups (of RBW * 16 rows) per workgroup
+  constexpr int UPT = 2 * TILE_U4 / NT;  // staged 16-byte units per thread and tile (K and V)
+  static_assert(KS == 1 || KS == 2, "a tile holds two chunks");
+  static_assert(UPT == 4 || UPT == 8, "4 or 8 wavefronts");
+  __shared__ uint4 lds[2][2 * TILE_U4];  // [buffer][K tile | V tile], 2 x 32 KiB; reused for the key-group merge
+  __shared__ float2 lds_ml[KS == 2 ? RG * RBW * 64 : 1];  // (max, sum) of key group 1 for that merge
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int split = blockIdx.x, row_tile = blockIdx.y, bz = blockIdx.z;
+  const int rg = wave % RG, kg = wave / RG;
+  // XCD-aware order: hardware hands consecutive workgroup ids to the 8 XCDs in turn
+  int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const int total = gridDim.x * gridDim.y * gridDim.z;
+  if ((total & 7) == 0) lin = (lin & 7) * (total >> 3) + (lin >> 3);
+  const int split = lin % n_splits;
+  const int row_tile = (lin / n_splits) % gridDim.y, bz = lin / (n_splits * gridDim.y);
   const int b = bz / Hkv, kvh = bz - b * Hkv;
   const int G = H / Hkv;
   const int P = seq_p[b], N = seq_n[b], T = P + N;
   const int n_tiles = (T + TILE - 1) / TILE;
-  // key ranges of equal cost: a tile that holds tree keys (mask work) counts as two prefix tiles
   const int n_plain = P / TILE;  // tiles entirely inside the prefix
+  // key ranges of equal cost: a tile that holds tree keys (mask work) counts as two prefix tiles
   const int cost_total = n_plain + 2 * (n_tiles - n_plain);
   auto tile_at_cost = [&](int c) { return c <= n_plain ? c : n_plain + (c - n_plain + 1) / 2; };
   const int t_begin = tile_at_cost((int)((int64_t)split * cost_total / n_splits));
   const int t_end = split + 1 == n_splits ? n_tiles : tile_at_cost((int)((int64_t)(split + 1) * cost_total / n_splits));
   const int VR = G * n_step;
-  const int vrb = row_tile * 4 + wave;
-  const bool active = vrb * 16 < VR;  // wavefront owns real rows
-  const int vr = vrb * 16 + (lane & 15);
-  const int quad = lane >> 4;
-  const int g = active ? vr / n_step : 0;
-  const int node = active ? vr - g * n_step : 0;
-  const uint4* kbase = kc + (int64_t)bz * cap * 16;  // 16 uint4 per key
+  const int vrb0 = (row_tile * RG + rg) * RBW;              // first row block of this wavefront
+  const int nrb = max(0, min(RBW, VR / 16 - vrb0));         // row blocks that hold rows
+  const int row_in = lane & 15, quad = lane >> 4;
+  const uint4* kbase = kc + (int64_t)bz * cap * 16;
   const uint4* vbase = vc + (int64_t)bz * cap * 16;
 
-  // global -> register -> LDS staging of one tile (kept in eight named registers per thread)
   struct Stage {
-    uint4 k0, k1, k2, k3, v0, v1, v2, v3;
+    uint4 k0, k1, k2, k3, v0, v1, v2, v3;  // UPT / 2 of each kind are used
   };
   auto load_tile = [&](int t) {
     const uint4* ks = kbase + (int64_t)t * TILE_U4 + tid;
     const uint4* vs = vbase + (int64_t)t * TILE_U4 + tid;
     Stage st;
-    st.k0 = ks[0];
-    st.k1 = ks[256];
-    st.k2 = ks[512];
-    st.k3 = ks[768];
-    st.v0 = vs[0];
-    st.v1 = vs[256];
-    st.v2 = vs[512];
-    st.v3 = vs[768];
+    st.k0 = ks[0], st.k1 = ks[NT];
+    st.v0 = vs[0], st.v1 = vs[NT];
+    if (UPT == 8) {
+      st.k2 = ks[2 * NT], st.k3 = ks[3 * NT];
+      st.v2 = vs[2 * NT], st.v3 = vs[3 * NT];
+    }
     return st;
   };
-  // the first tile is requested before anything else (mask row, queries): it has the longest way to come
+  auto store_tile = [&](int buf, const Stage& st) {
+    uint4* d = lds[buf] + tid;
+    d[0] = st.k0, d[NT] = st.k1;
+    d[TILE_U4] = st.v0, d[TILE_U4 + NT] = st.v1;
+    if (UPT == 8) {
+      d[2 * NT] = st.k2, d[3 * NT] = st.k3;
+      d[TILE_U4 + 2 * NT] = st.v2, d[TILE_U4 + 3 * NT] = st.v3;
+    }
+  };
+  // the first tile is requested before anything else (queries, mask rows): it has the longest way to come
   Stage st_first;
   if (t_begin < t_end) st_first = load_tile(t_begin);
 
-  // this lane's row of the ancestor bitmask (4 words cover 256 tree slots), kept in registers
-  const uint64_t* mrow = mask + ((int64_t)b * n_step + node) * 4;
-  const uint64_t mw0 = mrow[0], mw1 = mrow[1], mw2 = mrow[2], mw3 = mrow[3];
-
-  f16x8_t q[8];  // [head-dim chunk kk][plane hi / lo]
-  if (active) {
+  f16x8_t q[RBW][4 * QP];
+  int node_of[RBW], g_of[RBW];
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) {
+    const int vrb = rb < nrb ? vrb0 + rb : 0;
     const uint4* qsrc = qp + (((int64_t)bz * (VR / 16) + vrb) * 8 << 6) + lane;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, qsrc[i << 6]);
-  } else {
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = __builtin_bit_cast(f16x8_t, make_uint4(0, 0, 0, 0));
+      for (int pl = 0; pl < QP; ++pl) q[rb][kk * QP + pl] = __builtin_bit_cast(f16x8_t, qsrc[(kk * 2 + pl) << 6]);
+    const int vr = vrb * 16 + row_in;
+    g_of[rb] = vr / n_step;
+    node_of[rb] = vr - g_of[rb] * n_step;
   }
-
-  f32x4_t o[8];
+  // o_l = ones . P^T: the running sum of each row's weights, present in every element
+  f32x4_t o[RBW][8], o_l[RBW];
+  float m_run[RBW];
 #pragma unroll
-  for (int hb = 0; hb < 8; ++hb) o[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float m_run = NEG_BIG, l_run = 0.f;
-
-  auto store_tile = [&](int buf, const Stage& st) {
-    uint4* d = lds[buf] + tid;
-    d[0] = st.k0;
-    d[256] = st.k1;
-    d[512] = st.k2;
-    d[768] = st.k3;
-    d[TILE_U4] = st.v0;
-    d[TILE_U4 + 256] = st.v1;
-    d[TILE_U4 + 512] = st.v2;
-    d[TILE_U4 + 768] = st.v3;
-  };
-
-  DED_APHASE_DECL
-  auto compute_tile = [&](int buf, int t) {
-    DED_APHASE_START
-    const uint4* lk = lds[buf];
-    const uint4* lv = lds[buf] + TILE_U4;
-    // S^T: s[kb][c][i] = score of key  t*64 + kb*32 + quad*8 + c*4 + i  against this lane's row
-    f32x4_t s[2][2];
+  for (int rb = 0; rb < RBW; ++rb) {
+    m_run[rb] = NEG_BIG;
+    o_l[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int hb = 0; hb < 8; ++hb) o[rb][hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  const f16x8_t ones = f16_ones();
+
+  // one 32-key chunk (kb = 0, 1) of the tile in LDS buffer `buf` against the wavefront's rows
+  auto compute_chunk = [&](int buf, int t, int kb) {
+    const uint4* lk = lds[buf] + ((kb * 8) << 6) + lane;
+    const uint4* lv = lds[buf] + TILE_U4 + ((kb * 8) << 6) + lane;
+    const int key0 = t * TILE + kb * CHUNK;
+    const bool plain = key0 + CHUNK <= P;  // whole chunk inside the prefix: every key visible to every row
+    f16x8_t kf[8];
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
+    for (int i = 0; i < 8; ++i) kf[i] = __builtin_bit_cast(f16x8_t, lk[i << 6]);
+    f16x8_t pb[RBW];
+    float alpha[RBW];
+    bool rescale = false;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      // S^T: s[c2][i] = score of key  key0 + quad*8 + c2*4 + i  against row (vrb0 + rb)*16 + row_in
+      f32x4_t s[2];
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2) {
         f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
         f32x4_t acc_lo = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          f16x8_t a = __builtin_bit_cast(f16x8_t, lk[(((kb * 2 + c) * 4 + kk) << 6) + lane]);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, q[2 * kk], acc, 0, 0, 0);
-          acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, q[2 * kk + 1], acc_lo, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[c2 * 4 + kk], q[rb][kk * QP], acc, 0, 0, 0);
+          if (QP == 2) acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[c2 * 4 + kk], q[rb][kk * QP + QP - 1], acc_lo, 0, 0, 0);
         }
-        s[kb][c] = acc + acc_lo;
+        s[c2] = QP == 2 ? acc + acc_lo : acc;
       }
-    DED_APHASE(0)
-    const int key0 = t * TILE;
-    float p[2][8];
-    float mx = NEG_BIG;
-    if (key0 + TILE <= P) {  // whole tile inside the prefix: every key visible
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          p[kb][j] = s[kb][j >> 2][j & 3] * scale_log2e;
-          mx = fmaxf(mx, p[kb][j]);
-        }
-    } else {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          int key = key0 + kb * 32 + quad * 8 + j;
-          const int tt = key - P;  // tree slot of this key (negative inside the prefix)
-          const int wi = tt >> 6;
-          const uint64_t word = wi == 0 ? mw0 : wi == 1 ? mw1 : wi == 2 ? mw2 : mw3;
-          const bool vis = (key < P) | ((key < T) & (bool)((word >> (tt & 63)) & 1ull));  // no short circuit: no branches
-          float v = vis ? s[kb][j >> 2][j & 3] * scale_log2e : NEG_BIG;
-          p[kb][j] = v;
-          mx = fmaxf(mx, v);
-        }
+      softmax_chunk(s, plain, key0, quad, P, T, mask + ((int64_t)b * n_step + node_of[rb]) * 4, scale_log2e,
+                    m_run[rb], alpha[rb], pb[rb]);
+      rescale |= alpha[rb] != 1.0f;
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    float lsum = 0.f;
-    f16x8_t pb[2];
+    if (__any(rescale)) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+      for (int rb = 0; rb < RBW; ++rb) {
+        o_l[rb] *= alpha[rb];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        float e = p[kb][j] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(p[kb][j] - m_new) : 0.f;
-        _Float16 h = (_Float16)e;
-        lsum += (float)h;  // the sum uses the rounded weights the product uses
-        pb[kb][j] = h;
+        for (int hb = 0; hb < 8; ++hb) o[rb][hb] *= alpha[rb];
       }
     }
-    l_run = l_run * alpha + lsum;
-    m_run = m_new;
-    DED_APHASE(1)
-    if (__any(alpha != 1.0f)) {
 #pragma unroll
-      for (int hb = 0; hb < 8; ++hb) o[hb] *= alpha;
+    for (int rb = 0; rb < RBW; ++rb) o_l[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, pb[rb], o_l[rb], 0, 0, 0);
+#pragma unroll
+    for (int hb = 0; hb < 8; ++hb) {
+      const f16x8_t a = __builtin_bit_cast(f16x8_t, lv[hb << 6]);
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) o[rb][hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[rb], o[rb][hb], 0, 0, 0);
     }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int hb = 0; hb < 8; ++hb) {
-        f16x8_t a = __builtin_bit_cast(f16x8_t, lv[((kb * 8 + hb) << 6) + lane]);
-        o[hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[kb], o[hb], 0, 0, 0);
-      }
-    DED_APHASE(2)
   };
 
-  DED_ASTAMP(0)
+  auto compute_tile = [&](int buf, int t) {
+    if (nrb > 0) {
+      if (KS == 2) {
+        compute_chunk(buf, t, kg);
+      } else {
+#pragma unroll 1
+        for (int kb = 0; kb < 2; ++kb) compute_chunk(buf, t, kb);
+      }
+    }
+  };
   if (t_begin < t_end) {
+    const int t_last = t_end - 1;  // fetches past the range re-read its last tile: in bounds, and no branches
     store_tile(0, st_first);
     __syncthreads();
-    DED_ASTAMP(1)
     int buf = 0;
     for (int t = t_begin; t < t_end; ++t) {
-      // the last iteration re-fetches its own tile (in bounds, L2 hit) so that the loop body is branch free
-      const int t_next = t + 1 < t_end ? t + 1 : t;
-      Stage st = load_tile(t_next);
-      if (active) compute_tile(buf, t);
+      const Stage st = load_tile(min(t + 1, t_last));
+      compute_tile(buf, t);
       store_tile(buf ^ 1, st);
       __syncthreads();
       buf ^= 1;
     }
   }
 
-  DED_ASTAMP(2)
-  DED_APHASE_FLUSH
-  if (active) {
-    float l = l_run;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    const int h = kvh * G + g;
-    const int64_t prow = (((int64_t)b * H + h) * n_splits + split) * n_step + node;
+  if (KS == 2) {
+    // key group 1 hands its (max, sum, O) to key group 0 of the same rows through LDS (every workgroup barrier of
+    // the loop has been passed by all wavefronts, so the tile buffers are free)
+    float4* xo = reinterpret_cast<float4*>(&lds[0][0]);  // [rg][rb][hb][lane]: RG * 16 KiB <= the two tile buffers
+    float2* xml = lds_ml;                                // [rg][rb][lane]
+    if (kg == 1) {
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        xml[(rg * RBW + rb) * 64 + lane] = make_float2(m_run[rb], o_l[rb][0]);
+#pragma unroll
+        for (int hb = 0; hb < 8; ++hb)
+          xo[((rg * RBW + rb) * 8 + hb) * 64 + lane] = make_float4(o[rb][hb][0], o[rb][hb][1], o[rb][hb][2], o[rb][hb][3]);
+      }
+    }
+    __syncthreads();
+    if (kg == 1) return;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      const float2 other = xml[(rg * RBW + rb) * 64 + lane];
+      const float M = fmaxf(m_run[rb], other.x);
+      const float w0 = __builtin_amdgcn_exp2f(m_run[rb] - M), w1 = __builtin_amdgcn_exp2f(other.x - M);
+      o_l[rb][0] = o_l[rb][0] * w0 + other.y * w1;
+      m_run[rb] = M;
+#pragma unroll
+      for (int hb = 0; hb < 8; ++hb) {
+        const float4 v = xo[((rg * RBW + rb) * 8 + hb) * 64 + lane];
+        o[rb][hb] = o[rb][hb] * w0 + f32x4_t{v.x, v.y, v.z, v.w} * w1;
+      }
+    }
+  }
+
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) {
+    if (rb >= nrb) continue;
+    const float l = o_l[rb][0];  // every element of the ones-row product holds the row's sum
+    const int h = kvh * G + g_of[rb];
+    if (o_final) {
+      // a single key range: nothing to merge, the row is normalised here and written as the O projection's input
+      // (hi / lo f16 in PackX; four consecutive features sit side by side inside a fragment)
+      const float inv = 1.0f / l;
+      const int r = b * n_step + node_of[rb];
+#pragma unroll
+      for (int hb = 0; hb < 8; ++hb) {
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) split_f16(o[rb][hb][i] * inv, hi[i], lo[i]);
+        const int feat = h * 128 + hb * 16 + quad * 4;
+        *reinterpret_cast<uint2*>(o_final + packx_index(r, feat, RB_total, 0)) =
+            make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+        *reinterpret_cast<uint2*>(o_final + packx_index(r, feat, RB_total, 1)) =
+            make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+      }
+      continue;
+    }
+    const int64_t prow = (((int64_t)b * H + h) * n_splits + split) * n_step + node_of[rb];
     float* po = part_o + prow * 128 + quad * 4;
 #pragma unroll
     for (int hb = 0; hb < 8; ++hb)
-      *reinterpret_cast<float4*>(po + hb * 16) = make_float4(o[hb][0], o[hb][1], o[hb][2], o[hb][3]);
-    if (quad == 0) part_ml[prow] = make_float2(m_run, l);
+      *reinterpret_cast<float4*>(po + hb * 16) = make_float4(o[rb][hb][0], o[rb][hb][1], o[rb][hb][2], o[rb][hb][3]);
+    if (quad == 0) part_ml[prow] = make_float2(m_run[rb], l);
   }
-  DED_ASTAMP(3)
 }
 
 // One thread per (row, query head, 4 head dims).  The key ranges are folded in index order, eight at a time, with
@@ -296,36 +398,63 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(bf16_t* __restrict
 
 }  // namespace
 
+// Shapes with few rows per kv head (up to two 64-row tiles) take the key-split kernel, the others the
+// LDS-staged one whose wavefronts split the rows.
+// Kernel shape by the rows per kv head (grouped query heads x padded tree rows): see tree_attn_tiled_kernel.
+enum { ATTN_T64 = 0, ATTN_T128 = 1, ATTN_T256 = 2 };
+static int attn_kernel_for(const StepMeta& m, const ModelDims& md) {
+  const int VR = (md.H / md.Hkv) * m.n_step;
+  return VR <= 64 ? ATTN_T64 : VR <= 128 ? ATTN_T128 : ATTN_T256;
+}
+static int attn_tile_rows(int kind) { return kind == ATTN_T256 ? 256 : kind == ATTN_T128 ? 128 : 64; }
+
 int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int64_t part_rows_cap) {
   const int G = md.H / md.Hkv;
-  const int row_tiles = (G * m.n_step + 63) / 64;
+  const int kind = attn_kernel_for(m, md);
+  const int row_tiles = (G * m.n_step + attn_tile_rows(kind) - 1) / attn_tile_rows(kind);
+  const int base = std::max(1, m.batch * md.Hkv * row_tiles);
   const int tiles = (max_p + m.n_step + TILE - 1) / TILE;
-  const int base = m.batch * md.Hkv * row_tiles;
-  int ns = std::max(1, 512 / std::max(base, 1));
-  ns = std::min(ns, std::max(1, tiles / 2));  // keep >= 2 tiles (128 keys) per range: each range re-reads the queries
+  // resident workgroups: two per CU for the 4-wavefront shape, one for the 8-wavefront ones; split the keys only as
+  // far as it takes to fill them, and keep >= 2 (4) tiles per range: each range re-reads the queries and writes partials
+  const int slots = kind == ATTN_T64 ? 512 : 256;
+  int ns = std::max(1, slots / base);
+  ns = std::min(ns, std::max(1, tiles / (kind == ATTN_T256 ? 4 : 2)));
   while (ns > 1 && (int64_t)m.batch * md.H * ns * m.n_step > part_rows_cap) --ns;
   return ns;
 }
 
-void bf16_tree_attention_partial(const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc, float* part_o,
-                                 float2* part_ml, int n_splits, const StepMeta& m, const ModelDims& md,
-                                 hipStream_t s) {
+void bf16_tree_attention(bf16_t* o_packed, int rows_pad, const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc,
+                         float* part_o, float2* part_ml, int n_splits, int q_planes, const StepMeta& m,
+                         const ModelDims& md, hipStream_t s) {
   if (md.hd != 128 || n_splits < 1 || m.rows <= 0) return;
   const int G = md.H / md.Hkv;
-  const int row_tiles = (G * m.n_step + 63) / 64;
+  const int VR = G * m.n_step;
+  const int kind = attn_kernel_for(m, md);
+  const int row_tiles = (VR + attn_tile_rows(kind) - 1) / attn_tile_rows(kind);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)md.hd);
-  hipLaunchKernelGGL(tree_attn_partial_kernel, dim3(n_splits, row_tiles, m.batch * md.Hkv), dim3(256), 0, s,
-                     reinterpret_cast<const uint4*>(q_packed), reinterpret_cast<const uint4*>(kc),
-                     reinterpret_cast<const uint4*>(vc), part_o, part_ml, m.mask, m.seq_p, m.seq_n, m.n_step, md.H,
-                     md.Hkv, md.cap, n_splits, scale_log2e);
-}
-
-void bf16_tree_attention_merge(bf16_t* o_packed, int rows_pad, const float* part_o, const float2* part_ml,
-                               int n_splits, const StepMeta& m, const ModelDims& md, hipStream_t s) {
-  if (m.rows <= 0) return;
-  const int total = m.rows * md.H * 32;
-  hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((total + 255) / 256), dim3(256), 0, s, o_packed, rows_pad / 16,
-                     part_o, part_ml, n_splits, m.n_step, md.H, total);
+  const dim3 grid(n_splits, row_tiles, m.batch * md.Hkv);
+  bf16_t* o_final = n_splits == 1 ? o_packed : nullptr;  // one key range: the kernel finishes the rows itself
+#define DED_ATTN_ARGS                                                                                              \
+  reinterpret_cast<const uint4*>(q_packed), reinterpret_cast<const uint4*>(kc), reinterpret_cast<const uint4*>(vc), \
+      part_o, part_ml, m.mask, m.seq_p, m.seq_n, m.n_step, md.H, md.Hkv, md.cap, n_splits, scale_log2e, o_final,   \
+      rows_pad / 16
+#define DED_ATTN_GO(NW, KS, RBW)                                                                                       \
+  if (q_planes == 1) hipLaunchKernelGGL((tree_attn_tiled_kernel<1, NW, KS, RBW>), grid, dim3(NW * 64), 0, s, DED_ATTN_ARGS); \
+  else hipLaunchKernelGGL((tree_attn_tiled_kernel<2, NW, KS, RBW>), grid, dim3(NW * 64), 0, s, DED_ATTN_ARGS);
+  if (kind == ATTN_T256) {
+    DED_ATTN_GO(8, 1, 2)
+  } else if (kind == ATTN_T128) {
+    DED_ATTN_GO(8, 2, 2)
+  } else {
+    DED_ATTN_GO(4, 1, 1)
+  }
+#undef DED_ATTN_GO
+#undef DED_ATTN_ARGS
+  if (n_splits > 1) {
+    const int total = m.rows * md.H * 32;
+    hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((total + 255) / 256), dim3(256), 0, s, o_packed, rows_pad / 16,
+                       part_o, part_ml, n_splits, m.n_step, md.H, total);
+  }
 }
 
 }  // namespace ded

@@ -610,9 +610,8 @@ int forward_bf16(ded_ctx* c, bool want_logits) {
     }
     int ns = bf16_attn_pick_splits(m, md, c->max_p, c->attn_part_rows);
     { ProfScope p(c, KC_TREE_ATTN);
-      bf16_tree_attention_partial(c->q_p, (const bf16_t*)c->kc[l], (const bf16_t*)c->vc[l], c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
-    { ProfScope p(c, KC_ATTN_MERGE);
-      bf16_tree_attention_merge(c->o_p, rows_pad, c->attn_part_o, c->attn_part_ml, ns, m, md, s); }
+      bf16_tree_attention(c->o_p, rows_pad, c->q_p, (const bf16_t*)c->kc[l], (const bf16_t*)c->vc[l], c->attn_part_o,
+                          c->attn_part_ml, ns, 2, m, md, s); }
     {
       GemmEpilogue e = base;
       e.kind = EPI_RESIDUAL;
@@ -1042,9 +1041,8 @@ static int tree_attention_common(ded_ctx* c, int32_t layer, int32_t batch, const
       bf16_scatter_tree_kv((bf16_t*)c->kc[layer], (bf16_t*)c->vc[layer], (const bf16_t*)k_tree, (const bf16_t*)v_tree, m, md, mn, s);
       bf16_pack_q(ws.q_p, (const bf16_t*)q, m, md, mn, s); }
     { ProfScope p(c, KC_TREE_ATTN);
-      bf16_tree_attention_partial(ws.q_p, (const bf16_t*)c->kc[layer], (const bf16_t*)c->vc[layer], ws.part_o, ws.part_ml, ns, m, md, s); }
-    { ProfScope p(c, KC_ATTN_MERGE);
-      bf16_tree_attention_merge(ws.o_p, rows_pad, ws.part_o, ws.part_ml, ns, m, md, s); }
+      bf16_tree_attention(ws.o_p, rows_pad, ws.q_p, (const bf16_t*)c->kc[layer], (const bf16_t*)c->vc[layer], ws.part_o,
+                          ws.part_ml, ns, 1, m, md, s); }
     { ProfScope p(c, KC_LAYOUT); bf16_unpack_o((bf16_t*)out, ws.o_p, rows_pad, m, md, mn, s); }
   } else {
     { ProfScope p(c, KC_LAYOUT);
@@ -1077,6 +1075,12 @@ int ded_tree_attention_static(ded_ctx* c, int32_t layer, int32_t batch, const in
 }
 
 size_t ded_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int ded_probe_stream_read(const void* device_buffer, size_t bytes, void* sink4, void* hip_stream) {
+  if (!device_buffer || !sink4 || bytes < 16 || reinterpret_cast<uintptr_t>(device_buffer) % 16) return DED_EINVAL;
+  launch_stream_read(device_buffer, bytes / 16 * 16, static_cast<uint32_t*>(sink4), reinterpret_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
 
 int ded_profile_enable(ded_ctx* c, int32_t on) {
   if (!c) return DED_EINVAL;

@@ -28,6 +28,8 @@ struct ModelDims {
 // ---- shared (both dtypes) --------------------------------------------------------------
 // cos/sin of pos[r] * base^(-2i/hd), i < hd/2, angles formed in fp64.  tab: [R][hd/2] float2.
 void launch_rope_table(float2* tab, const int32_t* pos, int rows, int hd, float base, hipStream_t s);
+// Measurement aid: streams `bytes` (multiple of 16) of device memory through the CUs once.
+void launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 // Per-row argmax (lowest index on exact ties) and top-1 minus top-2 over V fp32 logits; flag[r] != 0 when the
 // row holds a NaN or an infinity.
 void launch_argmax(const float* logits, int64_t row_stride, int rows, int V, int32_t* amax,
@@ -132,15 +134,15 @@ int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan);
 bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const bf16_t* w_packed, int rows_pad,
                int N, int K, int planes, const GemmPlan& plan, int* counters, const GemmEpilogue& epi,
                hipStream_t s);
-// Tree-masked attention, two launches: split-KV partials (running max, sum, unnormalised output per
-// key range), then the merge that writes PackX(o).  n_splits from bf16_attn_pick_splits.
-// part_o: [B][H][n_splits][n_step][hd] fp32, part_ml: [B][H][n_splits][n_step] float2 (max, sum).
+// Tree-masked attention: split-KV partials (running max, sum, unnormalised output per key range), then - when
+// there is more than one key range - the merge; the result is written as PackX(o), hi/lo, for the O projection.
+// n_splits from bf16_attn_pick_splits.  part_o: [B][H][n_splits][n_step][hd] fp32, part_ml: [B][H][n_splits][n_step]
+// float2 (max, sum).  q_planes: 2 = the queries are hi + lo pairs, 1 = their lo plane is known to be zero
+// (queries given as bf16).
 int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int64_t part_rows_cap);
-void bf16_tree_attention_partial(const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc, float* part_o,
-                                 float2* part_ml, int n_splits, const StepMeta& m, const ModelDims& md,
-                                 hipStream_t s);
-void bf16_tree_attention_merge(bf16_t* o_packed, int rows_pad, const float* part_o, const float2* part_ml,
-                               int n_splits, const StepMeta& m, const ModelDims& md, hipStream_t s);
+void bf16_tree_attention(bf16_t* o_packed, int rows_pad, const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc,
+                         float* part_o, float2* part_ml, int n_splits, int q_planes, const StepMeta& m,
+                         const ModelDims& md, hipStream_t s);
 void bf16_kv_compact(bf16_t* const* kc, bf16_t* const* vc, const int32_t* path, const int32_t* n_acc,
                      const StepMeta& m, const ModelDims& md, int stride, hipStream_t s);
 void bf16_kv_copy(bf16_t* kcache, bf16_t* vcache, bf16_t* k_plain, bf16_t* v_plain, bool to_cache,
