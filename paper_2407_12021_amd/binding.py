@@ -14,7 +14,8 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libded_verify.so")
+# DED_VERIFY_LIB names another build of the same library (the host-sanitizer build of the CPU test tier)
+LIB_PATH = os.environ.get("DED_VERIFY_LIB") or os.path.join(_HERE, "libded_verify.so")
 
 DED_OK, DED_EINVAL, DED_ETREE, DED_ETOKEN, DED_ECAP, DED_ESTATE, DED_EHIP, DED_ENOMEM, DED_ENONFINITE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 DED_F32, DED_BF16 = 0, 1

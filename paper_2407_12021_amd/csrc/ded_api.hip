@@ -323,9 +323,10 @@ size_t carve_workspace(const ded_config& c, char* base, ded_ctx* ctx) {
   int32_t* rowflag = w.take<int32_t>(z.max_rows_pad);
   // one block, so that a single copy brings a step's verdict to the host: nacc | seqflag | path | acctok
   int32_t* nacc = w.take<int32_t>((int64_t)c.max_batch * (2 + 2 * stride));
-  int32_t* seqflag = nacc + c.max_batch;
-  int32_t* path = seqflag + c.max_batch;
-  int32_t* acct = path + (int64_t)c.max_batch * stride;
+  // (no arithmetic on the null pointers of a sizing pass)
+  int32_t* seqflag = nacc ? nacc + c.max_batch : nullptr;
+  int32_t* path = nacc ? seqflag + c.max_batch : nullptr;
+  int32_t* acct = nacc ? path + (int64_t)c.max_batch * stride : nullptr;
   if (ctx) {
     ctx->d_meta = dmeta;
     ctx->meta_bytes = m;

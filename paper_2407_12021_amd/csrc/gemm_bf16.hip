@@ -60,6 +60,21 @@ typedef f32x4_t Acc[TN][4];  // one wavefront's tile: 4 feature tiles x 4 row bl
 // before the ticket is taken, and from the ticket's return value before the loads are issued.
 // A slice is private to the kernel, so it is kept in accumulator order: tile (row group, feature group) ->
 // (t, rb) -> half -> lane, 8 bytes each: every store / load instruction covers 512 contiguous bytes.
+// -DDED_SPLITK_FENCES builds the memory-model-only variant instead (plain slice accesses, a release fence before
+// the ticket and an acquire fence after it): the fallback should a future part or driver not give the
+// write-through / read-through behaviour of device-scope atomics that the default relies on.
+#ifdef DED_SPLITK_FENCES
+__device__ inline void slice_store(unsigned long long* p, unsigned long long v) { *p = v; }
+__device__ inline unsigned long long slice_load(const unsigned long long* p) { return *p; }
+#else
+__device__ inline void slice_store(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline unsigned long long slice_load(unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+#endif
+
 __device__ inline unsigned long long pack2(float a, float b) {
   return ((unsigned long long)__float_as_uint(b) << 32) | __float_as_uint(a);
 }
@@ -72,8 +87,8 @@ __device__ inline void store_slice(float* slice, int NG, int ng, int rb0, int la
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
       const f32x4_t v = acc[t][rb];
-      __hip_atomic_store(q + (t * 4 + rb) * 128, pack2(v[0], v[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(q + (t * 4 + rb) * 128 + 64, pack2(v[2], v[3]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      slice_store(q + (t * 4 + rb) * 128, pack2(v[0], v[1]));
+      slice_store(q + (t * 4 + rb) * 128 + 64, pack2(v[2], v[3]));
     }
 }
 
@@ -94,8 +109,8 @@ __device__ inline void load_slices(const float* part, int64_t part_stride, int s
     for (int t = 0; t < TN; ++t)
 #pragma unroll
       for (int j = 0; j < RBN; ++j) {
-        unsigned long long a = __hip_atomic_load(q + (t * 4 + j) * 128, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned long long b = __hip_atomic_load(q + (t * 4 + j) * 128 + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long a = slice_load(q + (t * 4 + j) * 128);
+        unsigned long long b = slice_load(q + (t * 4 + j) * 128 + 64);
         acc[t][j] += f32x4_t{__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)),
                              __uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32))};
       }
@@ -112,8 +127,8 @@ __device__ inline void store_slice_rows(float* slice, int NG, int ng, int rb0, i
 #pragma unroll
     for (int j = 0; j < RBN; ++j) {
       const f32x4_t v = acc[t][j];
-      __hip_atomic_store(q + (t * 4 + j) * 128, pack2(v[0], v[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(q + (t * 4 + j) * 128 + 64, pack2(v[2], v[3]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      slice_store(q + (t * 4 + j) * 128, pack2(v[0], v[1]));
+      slice_store(q + (t * 4 + j) * 128 + 64, pack2(v[2], v[3]));
     }
 }
 
@@ -134,8 +149,8 @@ __device__ inline void sum_other_slices(const float* part, int64_t part_stride, 
     for (int t = 0; t < TN; ++t)
 #pragma unroll
       for (int j = 0; j < RBN; ++j) {
-        a[k][t][j] = __hip_atomic_load(q + (t * 4 + j) * 128, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        b[k][t][j] = __hip_atomic_load(q + (t * 4 + j) * 128 + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a[k][t][j] = slice_load(q + (t * 4 + j) * 128);
+        b[k][t][j] = slice_load(q + (t * 4 + j) * 128 + 64);
       }
   }
   f32x4_t own[TN][RBN];
@@ -405,7 +420,11 @@ __device__ inline void run_epilogue(const GemmEpilogue& e, int ng, int N, int rb
 // Split-K hand-over (splits > 1), second part: called by the whole workgroup after its wavefronts have issued their
 // slice stores.  Returns true in the workgroup that arrived last for its output tile.
 __device__ inline bool take_ticket(int splits, int* counters, int* s_flag) {
+#ifdef DED_SPLITK_FENCES
+  __atomic_thread_fence(__ATOMIC_RELEASE);  // agent scope is the default of a thread fence in HIP device code
+#else
   __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): this wavefront's slice stores have completed
+#endif
   DED_STAMP(4)
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -416,6 +435,9 @@ __device__ inline bool take_ticket(int splits, int* counters, int* s_flag) {
     *s_flag = last;
   }
   __syncthreads();
+#ifdef DED_SPLITK_FENCES
+  if (*s_flag) __atomic_thread_fence(__ATOMIC_ACQUIRE);
+#endif
   DED_STAMP(5)
   return *s_flag != 0;
 }
@@ -943,10 +965,12 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
   }
 }
 
-// Debug knob: DED_GEMM_TUNE="nwn,splits" forces the kernel shape (nwn 0 = stream kernel).
+// Sweep knob, compiled in only with -DDED_GEMM_TUNE_ENV (never in the library build): the environment variable
+// DED_GEMM_TUNE="nwn,splits" forces the kernel shape (nwn 0 = stream kernel).
 struct Tune {
   int nwn = -1, splits = 0;
   Tune() {
+#ifdef DED_GEMM_TUNE_ENV
     if (const char* e = getenv("DED_GEMM_TUNE")) {
       int a = -1, b = 0;
       if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && a <= 4 && b >= 1) {
@@ -954,6 +978,7 @@ struct Tune {
         splits = b;
       }
     }
+#endif
   }
 };
 

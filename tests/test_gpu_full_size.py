@@ -176,3 +176,41 @@ def test_c3_shape_decode_loop_lossless():
     got = np.array(out[:n_new])
     print(f"decode loop: {steps} steps for {len(out)} tokens; oracle-sure positions {int(sure.sum())}/{n_new}")
     assert (got[sure] == a_ref[sure]).all()
+
+
+@pytest.mark.parametrize("shape", ["c3-width-64-rows", "batched-512-rows"])
+def test_split_k_hand_over_is_bit_reproducible_over_many_launches(shape):
+    """Every projection hands split-K slices from workgroup to workgroup inside one launch (device-scope relaxed
+    atomics, a wait for the stores, then a ticket); a stale slice would change logits silently.  The same step is
+    launched a few hundred times - 9 split GEMMs per step at the 7B width (wide, stream and LM-head plans), and the
+    large-row kernel's splits on a batched shape - and every launch's logits must equal the first one's bit for
+    bit; the run stops at the first mismatch."""
+    import torch
+    if shape == "c3-width-64-rows":
+        wl = di.WORKLOADS["c3"]
+        cfg, batch, nodes, P, reps = wl.model.with_layers(2), 1, 64, 192, 300
+    else:
+        cfg, batch, nodes, P, reps = di.ModelConfig("repro-b", 2, 1024, 8, 8, 128, 2816, 8192), 4, 128, 128, 120
+    w = di.make_weights(cfg, seed=0, threads=16)
+    ver = _verifier(cfg, w, max_batch=batch, kv_capacity=P + nodes + 8, max_nodes=nodes)
+    prefix = [di.zipf_tokens(cfg.vocab, P, seed=20 + b) for b in range(batch)]
+    for s in range(0, P, nodes):
+        n = min(nodes, P - s)
+        ver.verify_step([s] * batch, [di.chain_tree(n)] * batch, [p[s:s + n] for p in prefix])
+        ver.accept(mode=1)
+    parents = [di.random_tree(nodes, None, seed=30 + b) for b in range(batch)]
+    tokens = [di.zipf_tokens(cfg.vocab, nodes, seed=40 + b) for b in range(batch)]
+    first = ver.verify_step([P] * batch, parents, tokens, want_logits=True).clone()
+    a0, m0 = ver.get_argmax()
+    ver.accept(mode=0)
+    assert torch.isfinite(first).all()
+    for i in range(reps):
+        again = ver.verify_step([P] * batch, parents, tokens, want_logits=True)
+        assert torch.equal(again, first), f"launch {i + 1} differs from the first"
+        if i % 50 == 0:  # the fused top-2 path (no logits in memory) takes the same hand-over
+            ver.accept(mode=0)
+            ver.verify_step([P] * batch, parents, tokens)
+            a1, m1 = ver.get_argmax()
+            assert np.array_equal(a0, a1) and np.array_equal(m0, m1)
+        ver.accept(mode=0)
+    ver.close()

@@ -315,6 +315,9 @@ def test_random_planted_trees_over_three_steps():
             ref, kr, vr = oracle.verify_tree(cfg, w, parent, token, pk, pv)
             logits = ver.verify_step([P], [parent], [token], want_logits=True)[0, :n].cpu().numpy().astype(np.float64)
             err = np.abs(logits - ref).max()
+            # N(0, 0.15) weights give logits far wider than the benchmark's N(0, 0.02) (|logit| up to ~40): the bound
+            # here is this test's own, relative to the logit scale (1 % of the largest logit), NOT the absolute 2e-2
+            # of the benchmark configurations, which test_gpu_full_size / test_gpu_big_shapes assert as such
             assert err <= (1e-4 if dtype == "fp32" else 1e-2) * max(1.0, np.abs(ref).max()), (err, np.abs(ref).max())
             a_gpu, _ = ver.get_argmax()
             acc, path, newp = ver.accept(mode=0)
@@ -484,6 +487,7 @@ def test_zero_layer_bf16_gemm_path():
     a_gpu, _ = ver.get_argmax()
     for b, n in enumerate((40, 7)):
         ref, _, _ = oracle.verify_tree(cfg, w, parents[b], tokens[b])
+        # N(0, 0.3) LM-head weights: logits of width ~5; this test's own bound scales with them (see above)
         assert np.abs(logits[b, :n] - ref).max() <= 2e-2 * max(1.0, np.abs(ref).max() / 4)
         assert (a_gpu[b, :n] == np.argmax(logits[b, :n], axis=1)).all()
     ver.close()
