@@ -29,19 +29,19 @@ if ROOT not in sys.path:
 GEMM_CLASSES = ["gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head"]
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
-# HBM traffic per launch, KiB, as read by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --pmc-mode`
+# HBM traffic per launch, KiB, as read by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --profile-mode c3` and `--profile-mode c2`
 # (summary and commands: profiles/c3_verify_step_hbm_traffic_pmc.md).  A plain 1 GiB device copy in the same
 # run reads 0.5 GiB on FETCH_SIZE (wide coalesced loads are counted at half their size) and 1.0 GiB on
 # WRITE_SIZE, hence the factors.
 PMC_FETCH_FACTOR = 2.0
 PMC_WRITE_FACTOR = 1.0
 PMC_KIB = {  # class: (FETCH_SIZE, WRITE_SIZE) mean per launch
-    "gemm_qkv": (58235.0, 14346.0),
+    "gemm_qkv": (58226.0, 14346.0),
     "gemm_o": (21083.0, 6282.0),
-    "gemm_gate_up": (95108.0, 12395.0),
+    "gemm_gate_up": (95109.0, 12395.0),
     "gemm_down": (52187.0, 6282.0),
-    "gemm_lm_head": (136289.0, 24012.0),
-    "tree_attention_c2": (37473.0, 16640.0),
+    "gemm_lm_head": (136304.0, 16512.0),
+    "tree_attention_c2": (33601.0 + 8473.0, 16640.0 + 2048.0),  # split-KV kernel + merge kernel
 }
 
 
@@ -341,6 +341,34 @@ def large_rows_bench(di, steps=8):
             "frac": best["executed_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "cases": out}
 
 
+def profile_workload(di, mode):
+    """The launches that a rocprofv3 run of `--profile-mode` other than c3 should see (see the option's help)."""
+    import numpy as np
+    import torch
+    from paper_2407_12021_amd import Verifier
+    if mode == "c2":
+        attention_only_bench(di, iters=16)
+        return
+    if mode == "large":
+        cfg, batch, nodes, P = di.WORKLOADS["c3"].model.with_layers(2), 8, 256, 0
+    else:
+        cfg, batch, nodes, P = di.WORKLOADS["c5"].model.with_layers(2), 8, 256, 16384
+    w = di.make_weights(cfg, seed=0, threads=16)
+    ver = Verifier(cfg, w, max_batch=batch, kv_capacity=P + nodes + 64, max_nodes=nodes)
+    del w
+    g = np.random.default_rng(5)
+    for s0 in range(0, P, nodes):
+        ver.verify_step([s0] * batch, [di.chain_tree(nodes)] * batch, [g.integers(0, cfg.vocab, size=nodes) for _ in range(batch)])
+        ver.accept(mode=1)
+    parent = di.random_tree(nodes, None, seed=3)
+    toks = [g.integers(0, cfg.vocab, size=nodes) for _ in range(batch)]
+    for _ in range(4 if mode == "large" else 3):
+        ver.verify_step([P] * batch, [parent] * batch, toks)
+        ver.accept(mode=0)
+    torch.cuda.synchronize()
+    ver.close()
+
+
 STEP_LOWER_BOUND_MS = {"c3": 1.72, "c4": 6.2, "c5": 19.4}  # weight / cache bytes at 8 TB/s or matrix flops at 2.5 PFLOP/s
 
 
@@ -428,9 +456,12 @@ def main():
     ap.add_argument("--no-attn", action="store_true")
     ap.add_argument("--no-large-rows", action="store_true")
     ap.add_argument("--no-batched", action="store_true", help="skip the c4 / c5 step timings (26 GB and 15 GB of weights)")
-    ap.add_argument("--pmc-mode", action="store_true",
-                    help="for rocprofv3 --pmc runs: a 1 GiB torch copy (calibration), 2 verify steps and 2 attention-only "
-                         "launches, nothing else")
+    ap.add_argument("--profile-mode", choices=["c3", "c2", "large", "c5attn"],
+                    help="a minimal workload for rocprofv3 runs (kernel trace or one --pmc counter set), no timing: "
+                         "c3 = a 1 GiB device copy (counter calibration) + 4 verification steps of the benchmark workload; "
+                         "c2 = 24 attention-only launches of configuration 2; large = 4 steps of a 2-layer 7B-shape model "
+                         "on 8 x 256-node trees (2048 rows); c5attn = 3 steps of a 2-layer Llama-3-8B-shape model, batch 8, "
+                         "prefix 16384, 256-node trees")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -445,6 +476,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.profile_mode and args.profile_mode != "c3":
+        profile_workload(di, args.profile_mode)
+        print(json.dumps({"profile_mode": args.profile_mode}))
+        return
     wl = di.WORKLOADS["c3"]
     cfg = wl.model if not args.layers else wl.model.with_layers(args.layers)
     t0 = time.perf_counter()
@@ -462,17 +497,16 @@ def main():
         n = min(wl.n_nodes, P - s)
         ver.verify_step([s], [di.chain_tree(n)], [prefix[s:s + n]])
         ver.accept(mode=1)
-    if args.pmc_mode:
+    if args.profile_mode == "c3":
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
-        b.copy_(a)  # calibration: reads 1 GiB, writes 1 GiB
+        b.copy_(a)  # counter calibration: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
-        for _ in range(2):
+        for _ in range(4):
             ver.verify_step([P], [parent], [token])
             ver.accept(mode=0)
         ver.close()
-        attention_only_bench(di, iters=2)
-        print(json.dumps({"pmc_mode": True}))
+        print(json.dumps({"profile_mode": "c3"}))
         return
     planted = planted_trees(di, ver, wl, prefix, parent, token, seed=1)
 
@@ -607,7 +641,7 @@ def main():
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
                      "frac_of_measured_stream_read": gu_gbs / ceil["stream_read_gbs"],
                      "traffic": pmc_bytes("gemm_gate_up") if full_model else None,
-                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --pmc-mode` "
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --profile-mode c3` "
                                        "(profiles/c3_verify_step_hbm_traffic_pmc.md), not re-measured in this run",
                      "time_base": time_base,
                      "avg_launch_us": gu_us, "algorithmic_bytes_per_launch": gu_bytes,
