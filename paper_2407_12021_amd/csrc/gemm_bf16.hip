@@ -1027,20 +1027,24 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
   const int NG = (N + 16 * TN - 1) / (16 * TN), groups = K / (32 * PD), rg = rows_pad / 64;
   const int64_t w_bytes = (int64_t)NG * 64 * K * 2, slice = (int64_t)rows_pad * N * 4;
   if (rows_pad >= 256) {  // matrix-core bound: the large-row kernel
-    // One workgroup per CU is resident, so a launch runs in ceil(workgroups / CUs) rounds.  The two-group
-    // wavefront tile pays off with two-plane inputs once there are enough row tiles (measured: from ~1024 rows);
-    // k is split only as far as it takes to fill the last round (a split costs its slices: 15 % per extra slice).
-    const int gpw = (planes == 2 && rows_pad >= 1024) ? 2 : 1;
-    const int tiles = ((NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS) *
-                      ((rows_pad + 64 * large_row_groups(gpw) - 1) / (64 * large_row_groups(gpw)));
-    GemmPlan best{7 + gpw, 1, 1};
+    // One workgroup per CU is resident, so a launch runs in ceil(workgroups / CUs) rounds.
+    // Two wavefront tiles: one feature group per wavefront (256 features x 128 rows per workgroup: more workgroups)
+    // or two (256 x 256: a quarter to a third fewer LDS bytes per matrix instruction, which is what bounds this
+    // kernel; measured 15-18 % faster at equal CU filling).  k is split only as far as it takes to fill the last
+    // round (a split costs its slices: ~15 % per extra slice).  Two-plane inputs from 512 rows: both are weighed;
+    // otherwise the small tile (with single-plane inputs the large one measured 30-60 % slower).
+    GemmPlan best{8, 1, 1};
     double best_cost = 1e300;
-    for (int s = 1; s <= 4 && s <= max_splits && s <= groups; ++s) {
-      const int wgs = tiles * s, rounds = (wgs + kCUs - 1) / kCUs;
-      const double c = (double)rounds * kCUs / wgs * (1.0 + 0.15 * (s - 1));
-      if (c < best_cost) {
-        best_cost = c;
-        best.splits = s;
+    for (int gpw = 1; gpw <= ((planes == 2 && rows_pad >= 512) ? 2 : 1); ++gpw) {
+      const int tiles = ((NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS) *
+                        ((rows_pad + 64 * large_row_groups(gpw) - 1) / (64 * large_row_groups(gpw)));
+      for (int s = 1; s <= 4 && s <= max_splits && s <= groups; ++s) {
+        const int wgs = tiles * s, rounds = (wgs + kCUs - 1) / kCUs;
+        const double c = (double)rounds * kCUs / wgs * (1.0 + 0.15 * (s - 1)) * (gpw == 1 ? 1.15 : 1.0);
+        if (c < best_cost) {
+          best_cost = c;
+          best = GemmPlan{7 + gpw, 1, s};
+        }
       }
     }
     return best;

@@ -26,22 +26,26 @@ void launch_rope_table(float2* tab, const int32_t* pos, int rows, int hd, float 
 }
 
 // ------------------------------------------------------------------------------------------
-// Measurement aid: a plain streaming read (16 bytes per lane, grid-stride, four loads in flight per lane) of a
-// device buffer.  Its rate is the ceiling that a weight- or cache-streaming kernel can be held against on the
-// same chip in the same run.  The XOR of everything read goes to sink[0] so that the loads cannot be dropped.
+// Measurement aid: a plain streaming read of a device buffer: every wavefront walks a contiguous region of its own
+// with 16-byte loads, four in flight per lane (the access pattern of the weight-streaming GEMMs; interleaving the
+// wavefronts over the buffer instead is ~15 % slower on this chip).  Its rate is the ceiling that a weight- or
+// cache-streaming kernel can be held against on the same chip in the same run.  The XOR of everything read goes
+// to sink[0] so that the loads cannot be dropped.
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, int64_t n_u4,
                                                           uint32_t* __restrict__ sink) {
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+  const int64_t per = n_u4 / n_waves / 256 * 256;  // 16-byte units per wavefront, whole turns of 4 x 64 only
   uint4 a = make_uint4(0, 0, 0, 0);
-  for (; i + 3 * stride < n_u4; i += 4 * stride) {
-    const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+  const uint4* q = src + wave * per + lane;
+  for (int64_t i = 0; i < per; i += 256) {
+    const uint4 v0 = q[i], v1 = q[i + 64], v2 = q[i + 128], v3 = q[i + 192];
     a.x ^= v0.x ^ v1.x ^ v2.x ^ v3.x;
     a.y ^= v0.y ^ v1.y ^ v2.y ^ v3.y;
     a.z ^= v0.z ^ v1.z ^ v2.z ^ v3.z;
     a.w ^= v0.w ^ v1.w ^ v2.w ^ v3.w;
   }
-  for (; i < n_u4; i += stride) {
+  for (int64_t i = n_waves * per + wave * 64 + lane; i < n_u4; i += n_waves * 64) {  // what the regions leave over
     const uint4 v = src[i];
     a.x ^= v.x;
     a.y ^= v.y;
@@ -50,13 +54,13 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
   }
   uint32_t x = a.x ^ a.y ^ a.z ^ a.w;
   for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off);
-  if ((threadIdx.x & 63) == 0 && x == 0x9e3779b9u) sink[0] = x;  // practically never true: the store is the data dependence
+  if (lane == 0 && x == 0x9e3779b9u) sink[0] = x;  // practically never true: the store is the data dependence
 }
 
 void launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s) {
   const int64_t n = (int64_t)(bytes / 16);
   if (n <= 0) return;
-  hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 8), dim3(256), 0, s, reinterpret_cast<const uint4*>(src), n, sink);
+  hipLaunchKernelGGL(stream_read_kernel, dim3(1024), dim3(256), 0, s, reinterpret_cast<const uint4*>(src), n, sink);
 }
 
 // ------------------------------------------------------------------------------------------
