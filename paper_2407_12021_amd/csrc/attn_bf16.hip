@@ -398,9 +398,10 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(bf16_t* __restrict
 
 }  // namespace
 
-// Shapes with few rows per kv head (up to two 64-row tiles) take the key-split kernel, the others the
-// LDS-staged one whose wavefronts split the rows.
 // Kernel shape by the rows per kv head (grouped query heads x padded tree rows): see tree_attn_tiled_kernel.
+// Up to 64 rows: 4 row groups of 16 rows x 2 key groups; up to 128: 4 row groups of 32 rows x 2 key groups;
+// beyond: 8 row groups of 32 rows.  Eight wavefronts per workgroup in every shape: with four, the 64-row shape
+// left half of each CU's issue slots empty while it waited on the K/V stream (config 2: 25.6 -> 24.5 us).
 enum { ATTN_T64 = 0, ATTN_T128 = 1, ATTN_T256 = 2 };
 static int attn_kernel_for(const StepMeta& m, const ModelDims& md) {
   const int VR = (md.H / md.Hkv) * m.n_step;
@@ -414,9 +415,10 @@ int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int
   const int row_tiles = (G * m.n_step + attn_tile_rows(kind) - 1) / attn_tile_rows(kind);
   const int base = std::max(1, m.batch * md.Hkv * row_tiles);
   const int tiles = (max_p + m.n_step + TILE - 1) / TILE;
-  // resident workgroups: two per CU for the 4-wavefront shape, one for the 8-wavefront ones; split the keys only as
-  // far as it takes to fill them, and keep >= 2 (4) tiles per range: each range re-reads the queries and writes partials
-  const int slots = kind == ATTN_T64 ? 512 : 256;
+  // one workgroup per CU (a second set of key ranges costs more in partial outputs and merge time than it gains:
+  // config 2 is 1 us faster with 8 ranges than with 16); split the keys only as far as it takes to fill the CUs,
+  // and keep >= 2 (4) tiles per range: each range re-reads the queries and writes partials
+  const int slots = 256;
   int ns = std::max(1, slots / base);
   ns = std::min(ns, std::max(1, tiles / (kind == ATTN_T256 ? 4 : 2)));
   while (ns > 1 && (int64_t)m.batch * md.H * ns * m.n_step > part_rows_cap) --ns;
@@ -446,7 +448,7 @@ void bf16_tree_attention(bf16_t* o_packed, int rows_pad, const bf16_t* q_packed,
   } else if (kind == ATTN_T128) {
     DED_ATTN_GO(8, 2, 2)
   } else {
-    DED_ATTN_GO(4, 1, 1)
+    DED_ATTN_GO(8, 2, 1)
   }
 #undef DED_ATTN_GO
 #undef DED_ATTN_ARGS
