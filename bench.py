@@ -41,7 +41,7 @@ PMC_KIB = {  # class: (FETCH_SIZE, WRITE_SIZE) mean per launch
     "gemm_gate_up": (95109.0, 12395.0),
     "gemm_down": (52187.0, 6282.0),
     "gemm_lm_head": (136304.0, 16512.0),
-    "tree_attention_c2": (33601.0 + 8473.0, 16640.0 + 2048.0),  # split-KV kernel + merge kernel
+    "tree_attention_c2": (33615.0 + 4249.0, 8320.0 + 2048.0),  # split-KV kernel + merge kernel
 }
 
 
@@ -289,7 +289,7 @@ def attention_only_bench(di, iters=40):
             "achieved": whole, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": whole / HBM_PEAK_GBS,
             "traffic": pmc_bytes("tree_attention_c2"),
             "time_base": "one HIP-event bracket around the two launches of the operation (ded_profile_*); per-kernel "
-                         "durations: profiles/c2_tree_attention_kernel_stats.md",
+                         "durations: profiles/c2_tree_attention_kernel_stats_and_pmc.md",
             "us_per_launch": us, "algorithmic_bytes": alg}
 
 
