@@ -409,6 +409,10 @@ static int attn_kernel_for(const StepMeta& m, const ModelDims& md) {
 }
 static int attn_tile_rows(int kind) { return kind == ATTN_T256 ? 256 : kind == ATTN_T128 ? 128 : 64; }
 
+int bf16_attn_query_planes(const StepMeta& m, const ModelDims& md) {
+  return (md.H / md.Hkv) * m.n_step >= 512 ? 1 : 2;
+}
+
 int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int64_t part_rows_cap) {
   const int G = md.H / md.Hkv;
   const int kind = attn_kernel_for(m, md);

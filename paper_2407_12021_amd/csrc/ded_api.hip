@@ -612,7 +612,7 @@ int forward_bf16(ded_ctx* c, bool want_logits) {
     int ns = bf16_attn_pick_splits(m, md, c->max_p, c->attn_part_rows);
     { ProfScope p(c, KC_TREE_ATTN);
       bf16_tree_attention(c->o_p, rows_pad, c->q_p, (const bf16_t*)c->kc[l], (const bf16_t*)c->vc[l], c->attn_part_o,
-                          c->attn_part_ml, ns, 2, m, md, s); }
+                          c->attn_part_ml, ns, bf16_attn_query_planes(m, md), m, md, s); }
     {
       GemmEpilogue e = base;
       e.kind = EPI_RESIDUAL;

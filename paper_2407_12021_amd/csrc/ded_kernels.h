@@ -140,6 +140,11 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
 // float2 (max, sum).  q_planes: 2 = the queries are hi + lo pairs, 1 = their lo plane is known to be zero
 // (queries given as bf16).
 int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int64_t part_rows_cap);
+// Query planes the model path hands to the attention: 2, except 1 (hi plane only) when 512 or more rows share each
+// K / V byte (grouped query heads x tree rows per kv head): there the attention is bound by the matrix cores and the lo
+// plane is a third of their work, while the keys are stored with the same 11-bit rounding anyway, so the score error
+// grows by at most sqrt(2).
+int bf16_attn_query_planes(const StepMeta& m, const ModelDims& md);
 void bf16_tree_attention(bf16_t* o_packed, int rows_pad, const bf16_t* q_packed, const bf16_t* kc, const bf16_t* vc,
                          float* part_o, float2* part_ml, int n_splits, int q_planes, const StepMeta& m,
                          const ModelDims& md, hipStream_t s);
