@@ -110,9 +110,8 @@ __device__ __forceinline__ f16x8_t f16_ones() {
 // a tile; with KS = 2 a wavefront takes one chunk of every tile, so that few rows still spread over all
 // wavefronts, and the two key groups' (max, sum, O) are merged through LDS at the end, in key-group order.
 // Shapes in use (rows per workgroup tile = NW / KS * RBW * 16):
-//   64 rows  = 4 wavefronts x 16 rows, all keys each, two workgroups per CU: trees of one sequence, where a
-//              workgroup sees only a handful of tiles and a merge at its end would cost more than it saves;
-//   128 rows = 8 wavefronts as 4 row groups x 2 key groups;
+//   64 rows  = 8 wavefronts as 4 row groups of 16 rows x 2 key groups: trees of one sequence;
+//   128 rows = 8 wavefronts as 4 row groups of 32 rows x 2 key groups;
 //   256 rows = 8 wavefronts x 32 rows, all keys each: many rows per kv head (batched trees, grouped-query heads),
 //              where the matrix cores bound the operation and LDS bytes per matrix instruction decide how busy
 //              they are.
