@@ -442,9 +442,18 @@ def test_whole_loop_with_the_draft_maker_is_lossless(dtype):
     ver.close()
 
 
-@pytest.mark.parametrize("dtype,P,N,H,Hkv", [("fp32", 100, 20, 4, 2), ("bf16", 333, 50, 4, 2), ("bf16", 0, 16, 2, 2)])
+@pytest.mark.parametrize("dtype,P,N,H,Hkv", [
+    ("fp32", 100, 20, 4, 2),
+    ("bf16", 333, 50, 4, 2),     # 2 heads x 64 rows per kv head: the 128-row kernel shape, 3 key ranges
+    ("bf16", 0, 16, 2, 2),       # no prefix at all: one ragged tile of tree keys
+    ("bf16", 1500, 64, 2, 2),    # the 64-row shape, 8 key ranges, the last one holding the tree tile
+    ("bf16", 130, 100, 4, 4),    # 112 padded rows: the 128-row shape with an empty row block, 2 mask words
+    ("bf16", 700, 60, 8, 2),     # 4 heads x 64 rows per kv head: the 256-row shape, 3 key ranges
+    ("bf16", 64, 200, 2, 1),     # 2 heads x 208 rows: two 256-row tiles (the second ragged), 4 mask words
+])
 def test_tree_attention_only(dtype, P, N, H, Hkv):
-    """The attention layer on its own with injected q / K / V (config-2 style, small)."""
+    """The attention layer on its own with injected q / K / V (config-2 style, small); the 16-bit cases walk through
+    the kernel's three workgroup shapes, with and without key ranges, ragged row tiles and 1 - 4 mask words."""
     import torch
     hd = 128 if dtype == "bf16" else 64
     cfg = di.ModelConfig("attn-" + dtype, 1, 128, H, Hkv, hd, 128, 64, dtype=dtype)
