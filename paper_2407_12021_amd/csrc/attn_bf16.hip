@@ -418,13 +418,25 @@ int bf16_attn_pick_splits(const StepMeta& m, const ModelDims& md, int max_p, int
   const int row_tiles = (G * m.n_step + attn_tile_rows(kind) - 1) / attn_tile_rows(kind);
   const int base = std::max(1, m.batch * md.Hkv * row_tiles);
   const int tiles = (max_p + m.n_step + TILE - 1) / TILE;
-  // one workgroup per CU (a second set of key ranges costs more in partial outputs and merge time than it gains:
-  // config 2 is 1 us faster with 8 ranges than with 16); split the keys only as far as it takes to fill the CUs,
-  // and keep >= 2 (4) tiles per range: each range re-reads the queries and writes partials
-  const int slots = 256;
-  int ns = std::max(1, slots / base);
-  ns = std::min(ns, std::max(1, tiles / (kind == ATTN_T256 ? 4 : 2)));
-  while (ns > 1 && (int64_t)m.batch * md.H * ns * m.n_step > part_rows_cap) --ns;
+  // One workgroup per CU is resident (8 wavefronts of 150-250 registers), so a launch runs in rounds of 256
+  // workgroups; a round lasts its tiles plus a start-up of ~2.5 tile times (queries, first tile).  Splitting the
+  // keys costs the merge launch (~3 tile times) and the partials, written once and read once through memory
+  // (1 KiB per row and range at ~5.5 TB/s; a tile time is ~2 us).  Calibrated on configs 2-4: config 2 is 1 us
+  // faster with 8 ranges than with 16, the benchmark step's attention 4 % faster with 6 than with 8, and 160
+  // workgroups of 34 tiles with 128 rows each (config 4) are faster unsplit than as 480 workgroups of 12.
+  const int ns_max = std::min(16, std::max(1, tiles / (kind == ATTN_T256 ? 4 : 2)));  // >= 2 (4) tiles per range
+  const double rows_total = (double)m.batch * md.H * m.n_step;
+  int ns = 1;
+  double best = 1e300;
+  for (int n = 1; n <= ns_max; ++n) {
+    if (n > 1 && rows_total * n > (double)part_rows_cap) break;
+    const int rounds = (base * n + 255) / 256;
+    const double cost = rounds * ((tiles + n - 1) / n + 2.5) + (n > 1 ? 3.0 + n * rows_total * 1024.0 / 5.5e6 / 2.0 : 0.0);
+    if (cost < best) {
+      best = cost;
+      ns = n;
+    }
+  }
   return ns;
 }
 
