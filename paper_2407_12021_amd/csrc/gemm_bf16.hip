@@ -467,12 +467,13 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
   const int ng = blockIdx.x;
   const int split = blockIdx.y;
   const int rb0 = blockIdx.z * 4;
-  // this wavefront's k range, in groups of PD steps
-  const int groups = KT / PD;
+  // this wavefront's k range, in units of RING steps (the finest grain the loop allows: K = 11008 over 16
+  // wavefronts is 21 or 22 steps each, where whole groups of PD steps would give 20 or 24)
+  const int units = KT / RING;
   const int parts = splits * NW;
   const int gi = split * NW + wave;
-  const int g_begin = (int)((int64_t)gi * groups / parts);
-  const int g_end = (int)((int64_t)(gi + 1) * groups / parts);
+  const int g_begin = (int)((int64_t)gi * units / parts);
+  const int g_end = (int)((int64_t)(gi + 1) * units / parts);
 
   Acc acc;
 #pragma unroll
@@ -511,8 +512,8 @@ __global__ __launch_bounds__(NW * 64, 2) void gemm_stream_kernel(float* __restri
         }
     };
 
-    int kt = g_begin * PD;
-    const int kt_last = g_end * PD - RING;  // first step of the last ring-full (range length % RING == 0)
+    int kt = g_begin * RING;
+    const int kt_last = g_end * RING - RING;  // first step of the last ring-full
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j, kt + j);
     const int kt_ssq = kt_last - 8 * RING > kt ? kt_last - 8 * RING : kt;  // 8 ring turns before the end
