@@ -183,8 +183,9 @@ def test_split_k_hand_over_is_bit_reproducible_over_many_launches(shape):
     """Every projection hands split-K slices from workgroup to workgroup inside one launch (device-scope relaxed
     atomics, a wait for the stores, then a ticket); a stale slice would change logits silently.  The same step is
     launched a few hundred times - 9 split GEMMs per step at the 7B width (wide, stream and LM-head plans), and the
-    large-row kernel's splits on a batched shape - and every launch's logits must equal the first one's bit for
-    bit; the run stops at the first mismatch."""
+    large-row kernel's splits on a batched shape - alternating between two token sets, so that the slices a launch
+    finds in the buffer are never the ones it is about to write, and every launch's logits must equal the first
+    launch's with the same tokens bit for bit; the run stops at the first mismatch."""
     import torch
     if shape == "c3-width-64-rows":
         wl = di.WORKLOADS["c3"]
@@ -200,17 +201,23 @@ def test_split_k_hand_over_is_bit_reproducible_over_many_launches(shape):
         ver.accept(mode=1)
     parents = [di.random_tree(nodes, None, seed=30 + b) for b in range(batch)]
     tokens = [di.zipf_tokens(cfg.vocab, nodes, seed=40 + b) for b in range(batch)]
-    first = ver.verify_step([P] * batch, parents, tokens, want_logits=True).clone()
-    a0, m0 = ver.get_argmax()
-    ver.accept(mode=0)
-    assert torch.isfinite(first).all()
+    tokens_b = [di.zipf_tokens(cfg.vocab, nodes, seed=60 + b) for b in range(batch)]
+    first, am = [], []
+    for tk in (tokens, tokens_b):
+        first.append(ver.verify_step([P] * batch, parents, tk, want_logits=True).clone())
+        am.append(ver.get_argmax())
+        ver.accept(mode=0)
+        assert torch.isfinite(first[-1]).all()
+    assert not torch.equal(first[0], first[1])
     for i in range(reps):
-        again = ver.verify_step([P] * batch, parents, tokens, want_logits=True)
-        assert torch.equal(again, first), f"launch {i + 1} differs from the first"
-        if i % 50 == 0:  # the fused top-2 path (no logits in memory) takes the same hand-over
+        which = i & 1
+        tk = tokens_b if which else tokens
+        again = ver.verify_step([P] * batch, parents, tk, want_logits=True)
+        assert torch.equal(again, first[which]), f"launch {i + 1} differs from the first with these tokens"
+        if i % 50 < 2:  # the fused top-2 path (no logits in memory) takes the same hand-over
             ver.accept(mode=0)
-            ver.verify_step([P] * batch, parents, tokens)
+            ver.verify_step([P] * batch, parents, tk)
             a1, m1 = ver.get_argmax()
-            assert np.array_equal(a0, a1) and np.array_equal(m0, m1)
+            assert np.array_equal(am[which][0], a1) and np.array_equal(am[which][1], m1)
         ver.accept(mode=0)
     ver.close()
