@@ -692,46 +692,78 @@ __global__ __launch_bounds__(NWN * 128, 2) void gemm_wide_kernel(float* __restri
   ssq_clear(ssq);
   const int wv = threadIdx.x >> 6;
   const int c_ssq = n_chunks - 14;  // fetch the row sums ~10 iterations before the loop ends
-  WChunk w0 = load_w(0);
-  XStage x0 = load_x(0);
-  WChunk w1 = load_w(1);
-  int buf = 0;
   if constexpr (DEEP) {
-    XStage x1 = load_x(1);
-    WChunk w2 = w1;
-    if (n_chunks > 2) w2 = load_w(2);
-    store_x(0, x0);
+    // Weights three chunks ahead, activations two.  The ring slots are fixed registers (the loop is unrolled by the
+    // ring length and leaves from the middle): a copy between slots would have to wait for the load that still
+    // writes its source.  The loads go through volatile accesses: the compiler otherwise sinks a prefetch to the
+    // block of its first use, i.e. issues it one iteration before it is needed whatever the source says.  Fetches
+    // past the range re-read its last chunk (in bounds, never used).
+    const int c_max = n_chunks - 1;
+    auto cl = [&](int c) { return c < c_max ? c : c_max; };
+    auto ldv = [](const volatile uint4* q) {
+      uint4 r;
+      r.x = q->x, r.y = q->y, r.z = q->z, r.w = q->w;
+      return r;
+    };
+    auto load_w_pinned = [&](int c) {
+      WChunk w;
+#pragma unroll
+      for (int t = 0; t < TN; ++t) w.f[0][t] = ldv(wsrc + (((int64_t)(kt0 + c) * TN + t) << 6));
+      return w;
+    };
+    auto load_x_pinned = [&](int c) {
+      XStage x;
+#pragma unroll
+      for (int i = 0; i < PER_THREAD; ++i) {
+        int u = tid + i * TH;
+        if (CHUNK_U4 % TH != 0 && u >= CHUNK_U4) u = CHUNK_U4 - 1;  // surplus threads fetch the last unit again
+        x.u[i] = ldv(xsrc + (int64_t)(kt0 + c) * xstep + u);        // CH == 1, two planes: unit u of the step
+      }
+      return x;
+    };
+    static_assert(!DEEP || (CH == 1 && PLANES == 2), "the pinned loads assume one two-plane k step per chunk");
+    const int c_ssq4 = c_ssq > 0 ? c_ssq / 4 * 4 : 0;
+    XStage xa = load_x_pinned(0), xb;  // xa: even chunks, xb: odd chunks
+    WChunk w0 = load_w_pinned(0);
+    xb = load_x_pinned(cl(1));
+    WChunk w1 = load_w_pinned(cl(1));
+    WChunk w2 = load_w_pinned(cl(2));
+    WChunk w3;
+    store_x(0, xa);
     __syncthreads();
     DED_STAMP(1)
-    if (c_ssq < 0) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
-    for (int c = 0; c + 3 < n_chunks; ++c) {
-      XStage x2 = load_x(c + 2);
-      WChunk w3 = load_w(c + 3);
-      if (c == c_ssq) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
-      compute(w0, buf);
-      store_x(buf ^ 1, x1);
+    for (int c = 0;;) {
+      if (c == c_ssq4) ssq_issue(epi, rb0, lane, wv, 2 * NWN, ssq);
+      xa = load_x_pinned(cl(c + 2));
+      w3 = load_w_pinned(cl(c + 3));
+      compute(w0, 0);
+      store_x(1, xb);
       __syncthreads();
-      w0 = w1;
-      w1 = w2;
-      w2 = w3;
-      x1 = x2;
-      buf ^= 1;
-    }
-    if (n_chunks > 2) {  // third-last chunk: one more activation chunk to fetch, no weights
-      XStage x2 = load_x(n_chunks - 1);
-      compute(w0, buf);
-      store_x(buf ^ 1, x1);
+      if (++c >= n_chunks) break;
+      xb = load_x_pinned(cl(c + 2));
+      w0 = load_w_pinned(cl(c + 3));
+      compute(w1, 1);
+      store_x(0, xa);
       __syncthreads();
-      w0 = w1;
-      w1 = w2;
-      x1 = x2;
-      buf ^= 1;
+      if (++c >= n_chunks) break;
+      xa = load_x_pinned(cl(c + 2));
+      w1 = load_w_pinned(cl(c + 3));
+      compute(w2, 0);
+      store_x(1, xb);
+      __syncthreads();
+      if (++c >= n_chunks) break;
+      xb = load_x_pinned(cl(c + 2));
+      w2 = load_w_pinned(cl(c + 3));
+      compute(w3, 1);
+      store_x(0, xa);
+      __syncthreads();
+      if (++c >= n_chunks) break;
     }
-    compute(w0, buf);  // second-last
-    store_x(buf ^ 1, x1);
-    __syncthreads();
-    compute(w1, buf ^ 1);  // last
   } else {
+    WChunk w0 = load_w(0);
+    XStage x0 = load_x(0);
+    WChunk w1 = load_w(1);
+    int buf = 0;
     store_x(0, x0);
     __syncthreads();
     DED_STAMP(1)
