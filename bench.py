@@ -158,7 +158,7 @@ def measured_ceilings():
     gemm_tflops = 2.0 * m ** 3 / (statistics.median(times) * 1e-3) / 1e12
     del a, b, c
     torch.cuda.empty_cache()
-    return {"stream_read_gbs": read_gbs, "stream_read": "2 GiB, 16 B per lane, library probe kernel, median of 10",
+    return {"stream_read_gbs": read_gbs, "stream_read": "2 GiB, 16 B per lane, non-temporal loads, library probe kernel, median of 10",
             "library_gemm_tflops": gemm_tflops, "library_gemm": "bf16 8192 x 8192 x 8192 via torch.matmul, median of 10",
             "hbm_peak_gbs": HBM_PEAK_GBS, "mfma_peak_tflops": MFMA_BF16_PEAK_TFLOPS}
 

@@ -27,10 +27,15 @@ void launch_rope_table(float2* tab, const int32_t* pos, int rows, int hd, float 
 
 // ------------------------------------------------------------------------------------------
 // Measurement aid: a plain streaming read of a device buffer: every wavefront walks a contiguous region of its own
-// with 16-byte loads, four in flight per lane (the access pattern of the weight-streaming GEMMs; interleaving the
-// wavefronts over the buffer instead is ~15 % slower on this chip).  Its rate is the ceiling that a weight- or
+// with 16-byte non-temporal loads, four in flight per lane (the access pattern of the weight-streaming GEMMs; the
+// non-temporal hint is worth ~12 % on this chip: 6.8 against 6.0 TB/s).  Its rate is the ceiling that a weight- or
 // cache-streaming kernel can be held against on the same chip in the same run.  The XOR of everything read goes
 // to sink[0] so that the loads cannot be dropped.
+typedef unsigned probe_u32x4_t __attribute__((ext_vector_type(4)));
+__device__ inline uint4 probe_load(const uint4* q) {
+  const probe_u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const probe_u32x4_t*>(q));
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, int64_t n_u4,
                                                           uint32_t* __restrict__ sink) {
   const int lane = threadIdx.x & 63;
@@ -39,7 +44,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
   uint4 a = make_uint4(0, 0, 0, 0);
   const uint4* q = src + wave * per + lane;
   for (int64_t i = 0; i < per; i += 256) {
-    const uint4 v0 = q[i], v1 = q[i + 64], v2 = q[i + 128], v3 = q[i + 192];
+    const uint4 v0 = probe_load(q + i), v1 = probe_load(q + i + 64), v2 = probe_load(q + i + 128), v3 = probe_load(q + i + 192);
     a.x ^= v0.x ^ v1.x ^ v2.x ^ v3.x;
     a.y ^= v0.y ^ v1.y ^ v2.y ^ v3.y;
     a.z ^= v0.z ^ v1.z ^ v2.z ^ v3.z;
