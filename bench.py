@@ -36,11 +36,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # f16 and bf16 dense MFMA peak
 PMC_FETCH_FACTOR = 2.0
 PMC_WRITE_FACTOR = 1.0
 PMC_KIB = {  # class: (FETCH_SIZE, WRITE_SIZE) mean per launch
-    "gemm_qkv": (58226.0, 14346.0),
+    "gemm_qkv": (63005.0, 14346.0),
     "gemm_o": (21083.0, 6282.0),
-    "gemm_gate_up": (95109.0, 12395.0),
+    "gemm_gate_up": (98621.0, 12395.0),
     "gemm_down": (52187.0, 6282.0),
-    "gemm_lm_head": (136304.0, 16512.0),
+    "gemm_lm_head": (136299.0, 16512.0),
     "tree_attention_c2": (33615.0 + 4249.0, 8320.0 + 2048.0),  # split-KV kernel + merge kernel
 }
 
