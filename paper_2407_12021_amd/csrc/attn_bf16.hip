@@ -6,7 +6,7 @@
 // contiguous in the cache) are fetched with fully coalesced 16-byte loads, parked in LDS (double buffered) and
 // consumed by the wavefronts, each of which owns one or two blocks of 16 rows:
 //     S^T = K . Q^T           v_mfma_f32_16x16x32_f16, A = key fragment (LDS), B = query fragment (VGPR, hi + lo)
-//     online soft-max          per lane: 1 row, 8 keys of a 32-key chunk; row max via two wavefront shuffles
+//     online soft-max          per lane: 1 row, 8 keys of a 32-key chunk; row max via two lane swaps
 //     O^T += V^T . P^T         A = value fragment (LDS), B = weights straight from the S^T registers
 //     l   += 1^T . P^T         the weights' sum, by the matrix cores as well (a row of ones)
 // The key rows of a 32-key group are interleaved inside the two 16-row tiles (see packk_index) so that after the
@@ -16,6 +16,7 @@
 // Each workgroup writes (running max, sum, unnormalised output) per row; a second kernel merges the key ranges
 // in a fixed order and writes the output as hi/lo f16 in PackX for the O projection.
 #include <algorithm>
+#include <type_traits>
 
 #include "bf16_layout.h"
 #include "ded_kernels.h"
@@ -29,6 +30,18 @@ constexpr int TILE_U4 = 1024;    // uint4 units of one K (or V) tile: 64 keys * 
 constexpr float NEG_BIG = -1.0e30f;
 
 constexpr int CHUNK = 32;  // keys per chunk: the contraction length of one matrix instruction of the second product
+
+// maximum over the four lanes (lane ^ 16, lane ^ 32, lane ^ 48) that hold the keys of one row, by the row / half
+// swaps of this GPU: after swapping with a copy of itself, one result holds the even rows (lower half) twice, the
+// other the odd rows (upper half) twice
+__device__ __forceinline__ float quad_max(float v) {
+  unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  u = __float_as_uint(m);
+  const auto b = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
 
 // Online soft-max step of ONE row block (16 rows, one per lane & 15) over ONE 32-key chunk.  s[c2][i] is the raw
 // score (q . k, unscaled) of key key0 + quad * 8 + c2 * 4 + i against the lane's row.  Updates the row's running
@@ -47,8 +60,7 @@ __device__ __forceinline__ void softmax_chunk(const f32x4_t (&s)[2], bool plain,
   if (plain) {
     float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                      fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = quad_max(mx);
     const float m_new = fmaxf(m_run, mx * scale_log2e);
     alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
@@ -76,8 +88,7 @@ __device__ __forceinline__ void softmax_chunk(const f32x4_t (&s)[2], bool plain,
       p[j] = v;
       mx = fmaxf(mx, v);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = quad_max(mx);
     const float m_new = fmaxf(m_run, mx);
     alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
@@ -131,6 +142,7 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
   static_assert(UPT == 4 || UPT == 8, "4 or 8 wavefronts");
   __shared__ uint4 lds[2][2 * TILE_U4];  // [buffer][K tile | V tile], 2 x 32 KiB; reused for the key-group merge
   __shared__ float2 lds_ml[KS == 2 ? RG * RBW * 64 : 1];  // (max, sum) of key group 1 for that merge
+  __shared__ uint4 lds_k3[(KS == 1 && RBW == 2 && QP == 1) ? TILE_U4 : 1];  // third K slot of the pipelined prefix loop
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = wave % RG, kg = wave / RG;
   // XCD-aware order: hardware hands consecutive workgroup ids to the 8 XCDs in turn
@@ -274,7 +286,189 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
     store_tile(0, st_first);
     __syncthreads();
     int buf = 0;
-    for (int t = t_begin; t < t_end; ++t) {
+    int t = t_begin;
+    if constexpr (KS == 1 && RBW == 2 && QP == 1) {
+      // Many rows per kv head: the matrix cores and the soft-max arithmetic bound the kernel, each busy about half
+      // of the time when a wavefront runs  scores -> soft-max -> second product  strictly one after the other.  The
+      // tiles that lie inside the prefix (no mask work) therefore go through a software pipeline, one 32-key chunk
+      // per stage: while chunk c gets its weights (exp2, conversion) and its second product, the scores of chunk
+      // c + 1 are already there and their exponents and row maxima are formed behind the second product's matrix
+      // instructions; nothing in a stage waits for a matrix result issued in the same stage.  For that the K half of a
+      // tile is parked in LDS one tile ahead of its V half (three K slots, two V slots).
+      // The running maximum becomes a REFERENCE that is raised only when a row's exponent exceeds 8 (weights stay
+      // below 2^8 in f16; numerator and normaliser carry the same reference, so the quotient is unchanged): the
+      // rescale of the output tile is a rarely taken branch between the stages, not arithmetic in every chunk.  The
+      // scores are kept as exponents relative to the reference, so a row maximum is taken over results of fused
+      // multiply-adds (canonical numbers, no quieting moves), across the four lanes of a row with this GPU's lane
+      // swaps (no LDS round trip).  Measured on the Llama-3-8B shape (8 x 256 nodes, 16384-key prefixes): 704 ->
+      // 575 us per layer.
+      const int t_pipe = min(t_end, n_plain);  // tiles [t_begin, t_pipe) hold prefix keys only
+      const bool wg_full = (row_tile + 1) * (RG * RBW) <= VR / 16;  // the same for every wavefront (barriers differ)
+      if (wg_full && t_pipe - t_begin >= 2) {
+        static_assert(KS != 1 || RBW != 2 || QP != 1 || UPT == 4, "two units of K and two of V per thread and tile");
+        typedef f32x4_t Scores[RBW][2];
+        struct Half {
+          uint4 a, b;
+        };
+        auto load_half = [&](const uint4* base, int tt) {
+          const uint4* src = base + (int64_t)tt * TILE_U4 + tid;
+          Half h;
+          h.a = src[0], h.b = src[NT];
+          return h;
+        };
+        auto store_half = [&](uint4* slot, const Half& h) {
+          uint4* d = slot + tid;
+          d[0] = h.a, d[NT] = h.b;
+        };
+        // raw scores -> soft-max exponents relative to the rows' present reference, in place, and each row's largest
+        // exponent (the fused multiply-adds' results are canonical numbers, so the maxima need no quieting moves)
+        auto exponents = [&](Scores& s, float (&mx)[RBW]) {
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) {
+            const float neg_m = -m_run[rb];
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) s[rb][c2][i] = fmaf(s[rb][c2][i], scale_log2e, neg_m);
+            const float v = fmaxf(fmaxf(fmaxf(s[rb][0][0], s[rb][0][1]), fmaxf(s[rb][0][2], s[rb][0][3])),
+                                  fmaxf(fmaxf(s[rb][1][0], s[rb][1][1]), fmaxf(s[rb][1][2], s[rb][1][3])));
+            mx[rb] = quad_max(v);
+          }
+        };
+        auto weights = [&](const Scores& s, f16x8_t (&pb)[RBW]) {
+          typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+              const float e0 = __builtin_amdgcn_exp2f(s[rb][j >> 2][j & 3]);
+              const float e1 = __builtin_amdgcn_exp2f(s[rb][j >> 2][(j & 3) + 1]);
+              const h2_t h = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(e0, e1));
+              pb[rb][j] = h[0];
+              pb[rb][j + 1] = h[1];
+            }
+        };
+        auto v_frags = [&](int b_, int kb, f16x8_t (&vf)[8]) {
+          const uint4* lv = lds[b_] + TILE_U4 + ((kb * 8) << 6) + lane;
+#pragma unroll
+          for (int hb = 0; hb < 8; ++hb) vf[hb] = __builtin_bit_cast(f16x8_t, lv[hb << 6]);
+        };
+        auto pv = [&](const f16x8_t (&vf)[8], const f16x8_t (&pb)[RBW]) {
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) o_l[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, pb[rb], o_l[rb], 0, 0, 0);
+#pragma unroll
+          for (int hb = 0; hb < 8; ++hb)
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) o[rb][hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[hb], pb[rb], o[rb][hb], 0, 0, 0);
+        };
+        // a row whose largest exponent exceeds 8 gets a new reference (its present maximum): the output tile and the
+        // pending exponents of that row move with it
+        auto raise = [&](const float (&mx)[RBW], Scores& s) {
+          bool need = false;
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) need |= mx[rb] > 8.0f;
+          if (__any(need)) {
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) {
+              const float delta = mx[rb] > 8.0f ? mx[rb] : 0.f;
+              const float alpha = __builtin_amdgcn_exp2f(-delta);
+              m_run[rb] += delta;
+              o_l[rb] *= alpha;
+#pragma unroll
+              for (int hb = 0; hb < 8; ++hb) o[rb][hb] *= alpha;
+#pragma unroll
+              for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s[rb][c2][i] -= delta;
+            }
+          }
+        };
+        Scores sa, sb;  // scores of a tile's first / second chunk
+        float mx[RBW];
+        f16x8_t pb[RBW];
+        // K halves of tiles t, t + 1 and (being written) t + 2; the V half of tile t sits in lds[buf], t + 1 goes to
+        // lds[buf ^ 1].  A third K slot, because both K(t) (second chunk) and K(t + 1) (first chunk) are read in the
+        // iteration that parks K(t + 2).
+        uint4 *k_cur = lds[0], *k_next = lds[1], *k_free = lds_k3;
+        auto qk = [&](const uint4* kslot, int kb, Scores& s) {
+          const uint4* lk = kslot + ((kb * 8) << 6) + lane;
+          f16x8_t kf[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) kf[i] = __builtin_bit_cast(f16x8_t, lk[i << 6]);
+#pragma unroll
+          for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) {
+              f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+              for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[c2 * 4 + kk], q[rb][kk], acc, 0, 0, 0);
+              s[rb][c2] = acc;
+            }
+        };
+        {
+          const Half kn = load_half(kbase, min(t + 1, t_last));
+          qk(k_cur, 0, sa);
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) {  // first reference of a row: the maximum of its first chunk
+            const float v = fmaxf(fmaxf(fmaxf(sa[rb][0][0], sa[rb][0][1]), fmaxf(sa[rb][0][2], sa[rb][0][3])),
+                                  fmaxf(fmaxf(sa[rb][1][0], sa[rb][1][1]), fmaxf(sa[rb][1][2], sa[rb][1][3])));
+            m_run[rb] = quad_max(v) * scale_log2e;
+          }
+          exponents(sa, mx);
+          store_half(k_next, kn);
+          __syncthreads();
+        }
+        auto tile_body = [&](auto last_tag) {
+          constexpr bool LAST = decltype(last_tag)::value;  // last prefix tile: nothing of tile t + 1 is computed here
+          Half kn, vn;
+          if constexpr (!LAST) {
+            kn = load_half(kbase, min(t + 2, t_last));
+            vn = load_half(vbase, min(t + 1, t_last));
+          }
+          // first chunk of tile t, scores of its second chunk
+          {
+            f16x8_t vf[8];
+            qk(k_cur, 1, sb);
+            v_frags(buf, 0, vf);
+            __builtin_amdgcn_sched_barrier(0);  // the V fragments are requested before the exponentials start
+            weights(sa, pb);
+            pv(vf, pb);
+          }
+          exponents(sb, mx);
+          raise(mx, sb);
+          // second chunk of tile t, scores of the first chunk of tile t + 1
+          {
+            f16x8_t vf[8];
+            if constexpr (!LAST) qk(k_next, 0, sa);
+            v_frags(buf, 1, vf);
+            __builtin_amdgcn_sched_barrier(0);
+            weights(sb, pb);
+            pv(vf, pb);
+          }
+          if constexpr (!LAST) {
+            exponents(sa, mx);
+            store_half(k_free, kn);
+            store_half(lds[buf ^ 1] + TILE_U4, vn);
+          }
+          __syncthreads();
+          if constexpr (!LAST) raise(mx, sa);
+        };
+        for (; t + 1 < t_pipe; ++t) {
+          tile_body(std::false_type{});
+          uint4* const k_old = k_cur;
+          k_cur = k_next, k_next = k_free, k_free = k_old;
+          buf ^= 1;
+        }
+        tile_body(std::true_type{});
+        ++t;
+        if (t < t_end) {  // the general loop expects its first tile whole in lds[0]
+          store_tile(0, load_tile(t));
+          __syncthreads();
+          buf = 0;
+        }
+      }
+    }
+    for (; t < t_end; ++t) {
       const Stage st = load_tile(min(t + 1, t_last));
       compute_tile(buf, t);
       store_tile(buf ^ 1, st);
