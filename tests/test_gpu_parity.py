@@ -450,6 +450,9 @@ def test_whole_loop_with_the_draft_maker_is_lossless(dtype):
     ("bf16", 130, 100, 4, 4),    # 112 padded rows: the 128-row shape with an empty row block, 2 mask words
     ("bf16", 700, 60, 8, 2),     # 4 heads x 64 rows per kv head: the 256-row shape, 3 key ranges
     ("bf16", 64, 200, 2, 1),     # 2 heads x 208 rows: two 256-row tiles (the second ragged), 4 mask words
+    ("bf16", 2100, 256, 8, 2),   # 4 heads x 256 rows, 32 prefix tiles: the 256-row shape's pipelined prefix loop, in key
+                                 # ranges that start inside the prefix, end inside it or hold the tree tiles
+    ("bf16", 200, 128, 4, 1),    # 4 heads x 128 rows, one key range: 3 pipelined prefix tiles, then the masked tiles
 ])
 def test_tree_attention_only(dtype, P, N, H, Hkv):
     """The attention layer on its own with injected q / K / V (config-2 style, small); the 16-bit cases walk through
@@ -477,11 +480,15 @@ def test_tree_attention_only(dtype, P, N, H, Hkv):
     err = np.abs(got - ref).max()
     # outputs are O(1); bf16 output rounding alone is 2^-9 relative
     assert err <= (2e-5 if dtype == "fp32" else 2e-2), err
-    # K/V round trip through the library layout is exact
+    # K/V round trip through the library layout: exact for every value of magnitude >= 2^-14; the 16-bit cache holds
+    # f16, so a smaller bf16 value lands on the f16 subnormal grid (spacing 2^-24), at most 2^-25 away
     if P:
         k_back, v_back = ver.kv_load(0, 0, 0, P)
-        assert np.array_equal(k_back.float().cpu().numpy(), oracle.widen(x["k_prefix"]).astype(np.float32))
-        assert np.array_equal(v_back.float().cpu().numpy(), oracle.widen(x["v_prefix"]).astype(np.float32))
+        for back, sent in ((k_back, x["k_prefix"]), (v_back, x["v_prefix"])):
+            a, b = back.float().cpu().numpy(), oracle.widen(sent).astype(np.float32)
+            big = np.abs(b) >= 2.0 ** -14
+            assert np.array_equal(a[big], b[big])
+            assert np.abs(a - b).max() <= (2.0 ** -25 if dtype == "bf16" else 0.0)
     ver.close()
 
 
