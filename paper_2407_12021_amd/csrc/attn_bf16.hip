@@ -300,8 +300,8 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
       // rescale of the output tile is a rarely taken branch between the stages, not arithmetic in every chunk.  The
       // scores are kept as exponents relative to the reference, so a row maximum is taken over results of fused
       // multiply-adds (canonical numbers, no quieting moves), across the four lanes of a row with this GPU's lane
-      // swaps (no LDS round trip).  Measured on the Llama-3-8B shape (8 x 256 nodes, 16384-key prefixes): 704 ->
-      // 575 us per layer.
+      // swaps (no LDS round trip), and only in that branch: the test itself looks at each lane's own eight keys.
+      // Measured on the Llama-3-8B shape (8 x 256 nodes, 16384-key prefixes): 704 -> 548 us per layer.
       const int t_pipe = min(t_end, n_plain);  // tiles [t_begin, t_pipe) hold prefix keys only
       const bool wg_full = (row_tile + 1) * (RG * RBW) <= VR / 16;  // the same for every wavefront (barriers differ)
       if (wg_full && t_pipe - t_begin >= 2) {
@@ -320,8 +320,9 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
           uint4* d = slot + tid;
           d[0] = h.a, d[NT] = h.b;
         };
-        // raw scores -> soft-max exponents relative to the rows' present reference, in place, and each row's largest
-        // exponent (the fused multiply-adds' results are canonical numbers, so the maxima need no quieting moves)
+        // raw scores -> soft-max exponents relative to the rows' present reference, in place, and the largest
+        // exponent among each lane's eight keys (the fused multiply-adds' results are canonical numbers, so the maxima
+        // need no quieting moves; the four lanes of a row are only combined if some lane asks for a new reference)
         auto exponents = [&](Scores& s, float (&mx)[RBW]) {
 #pragma unroll
           for (int rb = 0; rb < RBW; ++rb) {
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
               for (int i = 0; i < 4; ++i) s[rb][c2][i] = fmaf(s[rb][c2][i], scale_log2e, neg_m);
             const float v = fmaxf(fmaxf(fmaxf(s[rb][0][0], s[rb][0][1]), fmaxf(s[rb][0][2], s[rb][0][3])),
                                   fmaxf(fmaxf(s[rb][1][0], s[rb][1][1]), fmaxf(s[rb][1][2], s[rb][1][3])));
-            mx[rb] = quad_max(v);
+            mx[rb] = v;
           }
         };
         auto weights = [&](const Scores& s, f16x8_t (&pb)[RBW]) {
@@ -361,8 +362,8 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
 #pragma unroll
             for (int rb = 0; rb < RBW; ++rb) o[rb][hb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[hb], pb[rb], o[rb][hb], 0, 0, 0);
         };
-        // a row whose largest exponent exceeds 8 gets a new reference (its present maximum): the output tile and the
-        // pending exponents of that row move with it
+        // a row with an exponent above 8 gets a new reference (its present maximum): the output tile and the pending
+        // exponents of that row move with it
         auto raise = [&](const float (&mx)[RBW], Scores& s) {
           bool need = false;
 #pragma unroll
@@ -370,7 +371,8 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
           if (__any(need)) {
 #pragma unroll
             for (int rb = 0; rb < RBW; ++rb) {
-              const float delta = mx[rb] > 8.0f ? mx[rb] : 0.f;
+              const float row_mx = quad_max(mx[rb]);
+              const float delta = row_mx > 8.0f ? row_mx : 0.f;
               const float alpha = __builtin_amdgcn_exp2f(-delta);
               m_run[rb] += delta;
               o_l[rb] *= alpha;
