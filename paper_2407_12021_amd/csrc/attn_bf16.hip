@@ -122,13 +122,14 @@ __device__ __forceinline__ f16x8_t f16_ones() {
 // wavefronts, and the two key groups' (max, sum, O) are merged through LDS at the end, in key-group order.
 // Shapes in use (rows per workgroup tile = NW / KS * RBW * 16):
 //   64 rows  = 8 wavefronts as 4 row groups of 16 rows x 2 key groups: trees of one sequence;
-//   128 rows = 8 wavefronts as 4 row groups of 32 rows x 2 key groups;
+//   128 rows = 8 wavefronts as 4 row groups of 32 rows x 2 key groups, or (one key range) 8 wavefronts x 16 rows;
 //   256 rows = 8 wavefronts x 32 rows, all keys each: many rows per kv head (batched trees, grouped-query heads),
 //              where the matrix cores bound the operation and LDS bytes per matrix instruction decide how busy
 //              they are.
 // Workgroup indices are remapped so that neighbours in (key range, row tile) order - which fetch the same K / V -
 // run on the same XCD and meet in its L2.
 // ------------------------------------------------------------------------------------------
+// (PIPE: the prefix tiles of shapes in which every wavefront takes all keys go through the software pipeline below)
 template <int QP, int NW, int KS, int RBW>
 __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
     const uint4* __restrict__ qp, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
@@ -142,7 +143,8 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
   static_assert(UPT == 4 || UPT == 8, "4 or 8 wavefronts");
   __shared__ uint4 lds[2][2 * TILE_U4];  // [buffer][K tile | V tile], 2 x 32 KiB; reused for the key-group merge
   __shared__ float2 lds_ml[KS == 2 ? RG * RBW * 64 : 1];  // (max, sum) of key group 1 for that merge
-  __shared__ uint4 lds_k3[(KS == 1 && RBW == 2 && QP == 1) ? TILE_U4 : 1];  // third K slot of the pipelined prefix loop
+  constexpr bool PIPE = KS == 1 && ((RBW == 2 && QP == 1) || RBW == 1);
+  __shared__ uint4 lds_k3[PIPE ? TILE_U4 : 1];  // third K slot of the pipelined prefix loop
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = wave % RG, kg = wave / RG;
   // XCD-aware order: hardware hands consecutive workgroup ids to the 8 XCDs in turn
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
     __syncthreads();
     int buf = 0;
     int t = t_begin;
-    if constexpr (KS == 1 && RBW == 2 && QP == 1) {
+    if constexpr (PIPE) {
       // Many rows per kv head: the matrix cores and the soft-max arithmetic bound the kernel, each busy about half
       // of the time when a wavefront runs  scores -> soft-max -> second product  strictly one after the other.  The
       // tiles that lie inside the prefix (no mask work) therefore go through a software pipeline, one 32-key chunk
@@ -305,7 +307,7 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
       const int t_pipe = min(t_end, n_plain);  // tiles [t_begin, t_pipe) hold prefix keys only
       const bool wg_full = (row_tile + 1) * (RG * RBW) <= VR / 16;  // the same for every wavefront (barriers differ)
       if (wg_full && t_pipe - t_begin >= 2) {
-        static_assert(KS != 1 || RBW != 2 || QP != 1 || UPT == 4, "two units of K and two of V per thread and tile");
+        static_assert(!PIPE || UPT == 4, "two units of K and two of V per thread and tile");
         typedef f32x4_t Scores[RBW][2];
         struct Half {
           uint4 a, b;
@@ -403,7 +405,14 @@ __global__ __launch_bounds__(NW * 64, 2) void tree_attn_tiled_kernel(
             for (int rb = 0; rb < RBW; ++rb) {
               f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-              for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[c2 * 4 + kk], q[rb][kk], acc, 0, 0, 0);
+              for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[c2 * 4 + kk], q[rb][kk * QP], acc, 0, 0, 0);
+              if constexpr (QP == 2) {  // the lo query plane in a chain of its own, as in the general loop
+                f32x4_t acc_lo = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                  acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[c2 * 4 + kk], q[rb][kk * QP + 1], acc_lo, 0, 0, 0);
+                acc = acc + acc_lo;
+              }
               s[rb][c2] = acc;
             }
         };
@@ -657,7 +666,15 @@ void bf16_tree_attention(bf16_t* o_packed, int rows_pad, const bf16_t* q_packed,
   if (kind == ATTN_T256) {
     DED_ATTN_GO(8, 1, 2)
   } else if (kind == ATTN_T128) {
-    DED_ATTN_GO(8, 2, 2)
+    // one key range per workgroup (enough sequences and heads to fill the chip: batched trees): 8 wavefronts x 16
+    // rows, all keys each, whose prefix tiles run through the software pipeline (69 -> 63 us per layer at 4 x 128 rows
+    // on 2048-key prefixes); split ranges are short and keep the shape that reads every K / V fragment from LDS once
+    // per two row blocks
+    if (n_splits == 1) {
+      DED_ATTN_GO(8, 1, 1)
+    } else {
+      DED_ATTN_GO(8, 2, 2)
+    }
   } else {
     DED_ATTN_GO(8, 2, 1)
   }
