@@ -128,6 +128,9 @@ struct GemmPlan {
                // 8, 9: large-row kernel (256 features x 128 / 256 rows per workgroup)
   int nw;      // stream kernel: wavefronts splitting the k range
   int splits;  // split-K slices
+  // large-row kernel only: x_main > 0 = two launches, the first x_main feature tiles (whole scheduling rounds)
+  // unsplit, the others with k split rem_splits ways so that they fill one more round
+  int x_main = 0, rem_splits = 0;
 };
 GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits = 8);
 int bf16_gemm_tiles(int rows_pad, int N, const GemmPlan& plan);

@@ -888,7 +888,11 @@ template <int PLANES, int EPI, int GPW>
 __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ part, int64_t part_stride,
                                                          const uint4* __restrict__ xp, const uint4* __restrict__ wp,
                                                          int RB, int N, int KT, int splits,
-                                                         int* __restrict__ counters, GemmEpilogue epi) {
+                                                         int* __restrict__ counters, GemmEpilogue epi, int x_off,
+                                                         int slice_ng) {
+  // x_off / slice_ng: a launch may cover only the feature tiles from x_off on (the remainder launch of a plan whose
+  // last scheduling round would be mostly empty; it splits k where the main launch does not); its slices are indexed
+  // by the feature group's offset inside that range, slice_ng groups per row group
   constexpr int FGS = LARGE_FEAT_GROUPS / GPW, RGS = large_row_groups(GPW);
   constexpr int CH = (PLANES == 2 && GPW == 2) ? 1 : 2;  // k steps per LDS stage
   static_assert(FGS * RGS == 8, "8 wavefronts");
@@ -906,7 +910,9 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fg = wave % FGS, rg = wave / FGS;
   const int NG = (N + 16 * TN - 1) / (16 * TN);
-  const int g_first = (blockIdx.x * FGS + fg) * GPW;  // first feature group of this wavefront
+  const int bx = blockIdx.x + x_off;
+  const int g_off = x_off * (FGS * GPW);
+  const int g_first = (bx * FGS + fg) * GPW;  // first feature group of this wavefront
   const int split = blockIdx.y;
   const int rb_tile = blockIdx.z * (RGS * 4);
   const int rbw = rb_tile + rg * 4;                 // first row block of this wavefront
@@ -925,7 +931,7 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
     const int ks = i / UPS, j = i % UPS;
     if (j < WUPS) {
       const int v = tid + j * 512;
-      const int g_raw = blockIdx.x * (FGS * GPW) + (v >> 8);
+      const int g_raw = bx * (FGS * GPW) + (v >> 8);
       off[i] = ((((int64_t)(g_raw < NG ? g_raw : NG - 1) * KT + ks) * TN) << 6) + (v & 255);
     } else {
       const int xu = tid + (j - WUPS) * 512;
@@ -1012,16 +1018,17 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(float* __restrict__ par
   if (splits > 1) {
 #pragma unroll
     for (int gw = 1; gw < GPW; ++gw)
-      if (rows_ok && g_first + gw < NG) store_slice(part + (int64_t)split * part_stride, NG, g_first + gw, rbw, lane, acc[gw]);
-    last = finish_split(part, part_stride, split, splits, counters, NG, g_first < NG ? g_first : NG - 1, rbw, lane,
-                        rows_ok && g_first < NG, acc[0], &s_flag);
+      if (rows_ok && g_first + gw < NG)
+        store_slice(part + (int64_t)split * part_stride, slice_ng, g_first + gw - g_off, rbw, lane, acc[gw]);
+    last = finish_split(part, part_stride, split, splits, counters, slice_ng, (g_first < NG ? g_first : NG - 1) - g_off, rbw,
+                        lane, rows_ok && g_first < NG, acc[0], &s_flag);
   }
   if (last && rows_ok) {
 #pragma unroll
     for (int gw = 0; gw < GPW; ++gw) {
       const int ng = g_first + gw;
       if (ng >= NG) continue;
-      if (splits > 1) load_slices<4>(part, part_stride, splits, NG, ng, rbw, 0, lane, acc[gw]);
+      if (splits > 1) load_slices<4>(part, part_stride, splits, slice_ng, ng - g_off, rbw, 0, lane, acc[gw]);
       run_epilogue<EPI, 4>(epi, ng, N, rbw, rbw, row_scale, lane, acc[gw]);
     }
   }
@@ -1063,9 +1070,24 @@ bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float*
 #define DED_ARGS part, part_stride, xp, wp, RB, N, KT, splits, counters, epi
   if (plan.nwn == 8 || plan.nwn == 9) {
     const int rgs = large_row_groups(plan.nwn - 7);
-    dim3 grid(((N + 16 * TN - 1) / (16 * TN) + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS, splits, (RB + 4 * rgs - 1) / (4 * rgs));
-    if (plan.nwn == 8) hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI, 1>), grid, dim3(512), 0, s, DED_ARGS);
-    else hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI, 2>), grid, dim3(512), 0, s, DED_ARGS);
+    const int NG = (N + 16 * TN - 1) / (16 * TN);
+    const int X = (NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS, Z = (RB + 4 * rgs - 1) / (4 * rgs);
+    auto go = [&](dim3 grid, int64_t stride, int n_splits, int x_off, int slice_ng) {
+      if (plan.nwn == 8)
+        hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI, 1>), grid, dim3(512), 0, s, part, stride, xp, wp, RB, N, KT,
+                           n_splits, counters, epi, x_off, slice_ng);
+      else
+        hipLaunchKernelGGL((gemm_large_kernel<PLANES, EPI, 2>), grid, dim3(512), 0, s, part, stride, xp, wp, RB, N, KT,
+                           n_splits, counters, epi, x_off, slice_ng);
+    };
+    if (plan.x_main > 0) {
+      // whole rounds unsplit, then the remaining feature tiles with k split so that they fill one more round
+      const int rem_ng = NG - plan.x_main * LARGE_FEAT_GROUPS;
+      go(dim3(plan.x_main, 1, Z), part_stride, 1, 0, NG);
+      go(dim3(X - plan.x_main, plan.rem_splits, Z), (int64_t)RB * 16 * rem_ng * (16 * TN), plan.rem_splits, plan.x_main, rem_ng);
+    } else {
+      go(dim3(X, splits, Z), part_stride, splits, 0, NG);
+    }
     return true;
   }
   const bool once = RB == 4;  // one 64-row group: every weight byte is read once
@@ -1111,6 +1133,23 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
         if (c < best_cost) {
           best_cost = c;
           best = GemmPlan{7 + gpw, 1, s};
+        }
+      }
+      // A last round that is at most half full: the whole rounds stay unsplit and only the feature tiles of the
+      // last one split k, 2 - 4 ways, into one more (shorter) round of their own (a second launch).  The cut has to
+      // fall between feature tiles: whole rounds x CUs must be a multiple of the row tiles.
+      const int X = (NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS, Z = tiles / X, full = tiles / kCUs;
+      if (max_splits >= 2 && full >= 1 && (full * kCUs) % Z == 0 && full * kCUs < tiles) {
+        const int x_main = full * kCUs / Z, rem = tiles - full * kCUs;
+        const int rs = std::min(std::min(4, groups), kCUs / rem);
+        if (rs >= 2) {
+          const double c = (full + (1.0 + 0.15 * (rs - 1)) / rs + 0.05) * kCUs / tiles * (gpw == 1 ? 1.15 : 1.0);
+          if (c < best_cost) {
+            best_cost = c;
+            best = GemmPlan{7 + gpw, 1, 1};
+            best.x_main = x_main;
+            best.rem_splits = rs;
+          }
         }
       }
     }
@@ -1166,6 +1205,14 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
   if (splits < 1 || splits > groups || !counters) return false;
   if (plan.nwn != 0 && plan.nwn < 8 && groups / splits < 2) return false;
   if (plan.nwn > 9 || (plan.nwn == 9 && planes == 1)) return false;
+  if (plan.x_main > 0) {  // remainder launch: its 2 - 4 compact slices must fit into one slice of the whole matrix
+    const int X = (NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS;
+    if (plan.nwn < 8 || splits != 1 || plan.x_main >= X || plan.rem_splits < 2 || plan.rem_splits > 4 ||
+        plan.rem_splits > groups)
+      return false;
+    const int64_t rem_ng = NG - (int64_t)plan.x_main * LARGE_FEAT_GROUPS;
+    if (plan.rem_splits * rows_pad * rem_ng * (16 * TN) > part_stride) return false;
+  }
   if (splits > 1 && part_stride < (int64_t)rows_pad * NG * 16 * TN) return false;
   if ((epi.kind == EPI_RESIDUAL || epi.kind == EPI_QKV || epi.kind == EPI_SILU) && N % 64) return false;
   int nw = plan.nw >= 4 ? 4 : plan.nw >= 2 ? 2 : 1;
