@@ -554,10 +554,14 @@ bool lm_head_bf16(ded_ctx* c, bool want_logits) {
   }
   const int64_t slice = (int64_t)rows_pad * round_up(md.V, 64);
   int cap = (int)std::min<int64_t>(8, c->part_elems / slice);
-  GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, 2, std::max(cap, 1));
+  // From 256 rows on the projection is bound by the matrix cores and reads the hi plane of its input alone: the lo
+  // plane matters for what is carried through the layers, not here, where one rounding of the final normalised input
+  // (2^-12 relative) moves a logit by ~2e-4.  Below, the weight stream bounds it and the lo product is free.
+  const int planes = rows_pad >= 256 ? 1 : 2;
+  GemmPlan plan = bf16_gemm_plan(rows_pad, md.V, d, planes, std::max(cap, 1));
   if (bf16_gemm_tiles(rows_pad, md.V, plan) > kGemmCounters) plan.splits = 1;
   ProfScope p(c, KC_GEMM_LM_HEAD);
-  return bf16_gemm(c->part, slice, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, 2, plan, c->counters, e,
+  return bf16_gemm(c->part, slice, c->y_p, (const bf16_t*)c->lm_head, rows_pad, md.V, d, planes, plan, c->counters, e,
                    c->stream);
 }
 

@@ -1090,6 +1090,10 @@ bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float*
     }
     return true;
   }
+  // the logits epilogues read a single plane only where the projection is matrix-bound (the large-row kernel above)
+  if constexpr (PLANES == 1 && (EPI == EPI_LOGITS || EPI == EPI_TOP2)) {
+    return false;
+  } else {
   const bool once = RB == 4;  // one 64-row group: every weight byte is read once
 #define DED_SKINNY(KERNEL, A, GRID, THREADS)                                                          \
   if (once) hipLaunchKernelGGL((KERNEL<A, PLANES, EPI, true>), GRID, dim3(THREADS), 0, s, DED_ARGS);   \
@@ -1107,6 +1111,7 @@ bool launch_shape(const GemmPlan& plan, dim3 grid_stream, dim3 grid_wide, float*
 #undef DED_SKINNY
 #undef DED_ARGS
   return true;
+  }
 }
 
 }  // namespace
@@ -1224,9 +1229,11 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
   switch (epi.kind) {
     case EPI_LOGITS:
       if (planes == 2) DED_GO(2, EPI_LOGITS);
+      if (plan.nwn >= 8) DED_GO(1, EPI_LOGITS);
       return false;
     case EPI_TOP2:
       if (planes == 2) DED_GO(2, EPI_TOP2);
+      if (plan.nwn >= 8) DED_GO(1, EPI_TOP2);
       return false;
     case EPI_QKV:
       if (planes == 2) DED_GO(2, EPI_QKV);
