@@ -456,7 +456,7 @@ def test_whole_loop_with_the_draft_maker_is_lossless(dtype):
 ])
 def test_tree_attention_only(dtype, P, N, H, Hkv):
     """The attention layer on its own with injected q / K / V (config-2 style, small); the 16-bit cases walk through
-    the kernel's three workgroup shapes, with and without key ranges, ragged row tiles and 1 - 4 mask words."""
+    the kernel's workgroup shapes, with and without key ranges, ragged row tiles and 1 - 4 mask words."""
     import torch
     hd = 128 if dtype == "bf16" else 64
     cfg = di.ModelConfig("attn-" + dtype, 1, 128, H, Hkv, hd, 128, 64, dtype=dtype)
