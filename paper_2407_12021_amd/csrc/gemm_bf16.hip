@@ -1124,12 +1124,15 @@ GemmPlan bf16_gemm_plan(int rows_pad, int N, int K, int planes, int max_splits) 
     // One workgroup per CU is resident, so a launch runs in ceil(workgroups / CUs) rounds.
     // Two wavefront tiles: one feature group per wavefront (256 features x 128 rows per workgroup: more workgroups)
     // or two (256 x 256: a quarter to a third fewer LDS bytes per matrix instruction, which is what bounds this
-    // kernel; measured 15-18 % faster at equal CU filling).  k is split only as far as it takes to fill the last
-    // round (a split costs its slices: ~15 % per extra slice).  Two-plane inputs from 512 rows: both are weighed;
-    // otherwise the small tile (with single-plane inputs the large one measured 30-60 % slower).
+    // kernel; measured 15-18 % faster at equal CU filling with two-plane inputs, ~30 % with single-plane ones, whose
+    // small tile reads twice the LDS bytes per matrix instruction).  k is split only as far as it takes to fill the
+    // last round (a split costs its slices: ~15 % per extra slice).  From 512 rows both tiles are weighed; the narrow
+    // single-plane projections (N = d) keep the small one - the large tile leaves them so few workgroups that k has
+    // to be split, which measured slower (Llama-3-8B shape, 2048 rows: O 101 -> 130 us) -, the LM head takes the
+    // large one (3.1 -> 2.2 ms per step at that shape).
     GemmPlan best{8, 1, 1};
     double best_cost = 1e300;
-    for (int gpw = 1; gpw <= ((planes == 2 && rows_pad >= 512) ? 2 : 1); ++gpw) {
+    for (int gpw = 1; gpw <= (rows_pad >= 512 ? 2 : 1); ++gpw) {
       const int tiles = ((NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS) *
                         ((rows_pad + 64 * large_row_groups(gpw) - 1) / (64 * large_row_groups(gpw)));
       for (int s = 1; s <= 4 && s <= max_splits && s <= groups; ++s) {
@@ -1209,7 +1212,7 @@ bool bf16_gemm(float* part, int64_t part_stride, const bf16_t* x_packed, const b
   const int splits = plan.splits;
   if (splits < 1 || splits > groups || !counters) return false;
   if (plan.nwn != 0 && plan.nwn < 8 && groups / splits < 2) return false;
-  if (plan.nwn > 9 || (plan.nwn == 9 && planes == 1)) return false;
+  if (plan.nwn > 9) return false;
   if (plan.x_main > 0) {  // remainder launch: its 2 - 4 compact slices must fit into one slice of the whole matrix
     const int X = (NG + LARGE_FEAT_GROUPS - 1) / LARGE_FEAT_GROUPS;
     if (plan.nwn < 8 || splits != 1 || plan.x_main >= X || plan.rem_splits < 2 || plan.rem_splits > 4 ||
