@@ -298,7 +298,8 @@ def large_rows_bench(di, steps=8):
     7B-shape layers (2 of them), batch 8 x 256-node trees = 2048 rows, and the 13B shape with batch 4 x 128 =
     512 rows; empty prefixes (the attention share does not matter here).  Times are HIP-event brackets per
     kernel class.  'executed' counts the hi and lo activation planes (two matrix instructions per useful one in
-    the QKV / gate-up / LM-head GEMMs), 'useful' counts 2 * rows * N * K once."""
+    the QKV / gate-up GEMMs; the LM head reads the hi plane alone from 256 rows on, like the O and down
+    projections), 'useful' counts 2 * rows * N * K once."""
     import numpy as np
     from paper_2407_12021_amd import Verifier
     out = []
@@ -323,7 +324,7 @@ def large_rows_bench(di, steps=8):
         R = batch * nodes
         d, F, V, qkv_n = cfg.d_model, cfg.d_ffn, cfg.vocab, (cfg.n_heads + 2 * cfg.n_kv_heads) * cfg.head_dim
         shapes = {"gemm_qkv": (qkv_n, d, 2), "gemm_o": (d, cfg.n_heads * cfg.head_dim, 1), "gemm_gate_up": (2 * F, d, 2),
-                  "gemm_down": (d, F, 1), "gemm_lm_head": (V, d, 2)}
+                  "gemm_down": (d, F, 1), "gemm_lm_head": (V, d, 1 if R >= 256 else 2)}
         per = {}
         useful = executed = ms_total = 0.0
         for c, (N, K, planes) in shapes.items():
